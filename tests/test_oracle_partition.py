@@ -1,0 +1,188 @@
+"""Pins for the oracle's block construction, partition and merge.
+
+Each check is against something other than the oracle: the membership-mask
+definition of Appendix A, NumPy fancy indexing, the closed-form parameter
+counts of Section 2.1 / the footnote in Section 1, and invariants (disjoint
+cover, no collisions, untouched unowned entries).
+"""
+import numpy as np
+import pytest
+
+import ist_inputs as gen
+from oracle import ist_oracle as orc
+
+
+def _cfg(dims, S, dtype="f32"):
+    return gen.ISTConfig("t", 1, tuple(dims), S=S, B=4, k=1, rounds=1, dtype=dtype)
+
+
+def _masks(perms, dims, S):
+    """m[l][s] in {0,1}^{N_l}, built from the perm positions, not from oracle.block."""
+    t = len(dims) - 1
+    m = []
+    for l in range(t + 1):
+        if l == 0 or l == t:
+            m.append(np.ones((S, dims[l]), dtype=np.int64))
+        else:
+            pos = np.empty(dims[l], dtype=np.int64)
+            pos[perms[l - 1]] = np.arange(dims[l])
+            w = dims[l] // S
+            m.append(np.stack([(pos // w == s).astype(np.int64) for s in range(S)]))
+    return m
+
+
+@pytest.mark.parametrize("dims,S", [((6, 8, 12, 5), 2), ((5, 12, 9, 6, 3), 3), ((7, 16, 4), 4),
+                                    ((3, 5, 7, 2), 1)])
+def test_blocks_are_a_disjoint_cover(dims, S):
+    cfg = _cfg(dims, S)
+    perms = gen.make_perms(cfg)
+    H = orc.blocks(perms, S)
+    for l in range(1, cfg.t):
+        allb = np.concatenate(H[l - 1])
+        assert all(len(h) == dims[l] // S for h in H[l - 1])
+        assert np.array_equal(np.sort(allb), np.arange(dims[l]))   # each neuron exactly once
+    m = _masks(perms, dims, S)
+    for l in range(cfg.t + 1):
+        want = S if l in (0, cfg.t) else 1                         # sum_s m^{(s)}_{l,i}
+        assert np.all(m[l].sum(axis=0) == want)
+        if 0 < l < cfg.t:
+            for s in range(S):
+                assert np.array_equal(np.flatnonzero(m[l][s]), np.sort(H[l - 1][s]))
+
+
+def test_block_rejects_indivisible_width():
+    with pytest.raises(ValueError):
+        orc.block(np.arange(10, dtype=np.int32), 3, 0)
+
+
+@pytest.mark.parametrize("dims,S", [((6, 8, 12, 5), 2), ((5, 12, 9, 6, 3), 3), ((7, 16, 4), 4)])
+def test_partition_equals_masked_definition_and_numpy(dims, S):
+    cfg = _cfg(dims, S)
+    Ws, bs = gen.make_weights(cfg, bias_scale=0.3)
+    perms = gen.make_perms(cfg)
+    subs = orc.partition(Ws, bs, perms, S)
+    H = orc.blocks(perms, S)
+    m = _masks(perms, dims, S)
+    t = cfg.t
+    for s in range(S):
+        for l in range(1, t + 1):
+            rows = np.arange(dims[l]) if l == t else H[l - 1][s]
+            cols = np.arange(dims[l - 1]) if l == 1 else H[l - 2][s]
+            # (i) library routine as an independent opinion
+            assert np.array_equal(subs[s][0][l - 1], Ws[l - 1][np.ix_(rows, cols)])
+            # (ii) embedding the block in zeros equals (m_l m_{l-1}^T) * W_l
+            emb = np.zeros_like(Ws[l - 1])
+            emb[np.ix_(rows, cols)] = subs[s][0][l - 1]
+            assert np.array_equal(emb, np.outer(m[l][s], m[l - 1][s]) * Ws[l - 1])
+            assert np.array_equal(subs[s][1][l - 1], bs[l - 1][rows])
+
+
+def test_parameter_counts_match_closed_form():
+    dims, S = (6, 8, 12, 16, 5), 4
+    cfg = _cfg(dims, S)
+    Ws, bs = gen.make_weights(cfg)
+    subs = orc.partition(Ws, bs, gen.make_perms(cfg), S)
+    t = cfg.t
+    closed = dims[0] * dims[1] // S + sum(dims[i - 1] * dims[i] // S ** 2 for i in range(2, t)) \
+        + dims[t - 1] * dims[t] // S
+    full = sum(dims[i - 1] * dims[i] for i in range(1, t + 1))
+    for s in range(S):
+        assert sum(w.size for w in subs[s][0]) == closed
+    assert full / S ** 2 <= closed <= full / S
+    # the benchmark table: parameters per subnet of the five workloads
+    want = {"cfg1": 8832, "cfg2": 2132992, "cfg3": 4204544, "cfg4": 168591360, "cfg5": 103168000}
+    for name, c in gen.CONFIGS.items():
+        d, S_ = c.dims, c.S
+        p = d[0] * d[1] // S_ + sum(d[i - 1] * d[i] // S_ ** 2 for i in range(2, c.t)) \
+            + d[c.t - 1] * d[c.t] // S_
+        assert p == want[name]
+
+
+def test_single_hidden_layer_owns_every_weight():
+    dims, S = (7, 16, 4), 4
+    cfg = _cfg(dims, S)
+    Ws, bs = gen.make_weights(cfg)
+    subs = orc.partition(Ws, bs, gen.make_perms(cfg), S)
+    assert sum(w.size for s in range(S) for w in subs[s][0]) == sum(w.size for w in Ws)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_merge_of_partition_is_identity_bitwise(dtype):
+    dims, S = (5, 12, 8, 6, 3), 2
+    cfg = _cfg(dims, S, dtype)
+    Ws, bs = gen.make_weights(cfg, bias_scale=0.2)
+    if dtype == "bf16":
+        Ws = [gen.to_bf16_bits(w).reshape(w.shape) for w in Ws]      # raw 2-byte elements
+        bs_raw = [gen.to_bf16_bits(b) for b in bs]
+        W0 = [w.copy() for w in Ws]
+        subs = orc.partition(Ws, bs_raw, gen.make_perms(cfg), S)
+        for w in Ws:
+            w[...] = 0xFFFF
+        # weights only: merge() averages the float output bias, checked elsewhere
+        orc.merge(Ws, None, gen.make_perms(cfg), S, subs)
+        H = orc.blocks(gen.make_perms(cfg), S)
+        owned = [np.zeros(w.shape, bool) for w in Ws]
+        for s in range(S):
+            for l in range(1, cfg.t + 1):
+                rows = np.arange(dims[l]) if l == cfg.t else H[l - 1][s]
+                cols = np.arange(dims[l - 1]) if l == 1 else H[l - 2][s]
+                owned[l - 1][np.ix_(rows, cols)] = True
+        for w, w0, ow in zip(Ws, W0, owned):
+            assert np.array_equal(w[ow], w0[ow]) and np.all(w[~ow] == 0xFFFF)
+        return
+    W0 = [w.copy() for w in Ws]
+    b0 = [b.copy() for b in bs]
+    perms = gen.make_perms(cfg)
+    subs = orc.partition(Ws, bs, perms, S)
+    orc.merge(Ws, bs, perms, S, subs)
+    for a, b in zip(Ws + bs, W0 + b0):
+        assert a.tobytes() == b.tobytes()
+
+
+def test_merge_leaves_unowned_entries_and_never_collides():
+    dims, S = (5, 12, 8, 6, 3), 2
+    cfg = _cfg(dims, S)
+    Ws, bs = gen.make_weights(cfg)
+    perms = gen.make_perms(cfg)
+    subs = orc.partition(Ws, bs, perms, S)
+    # distinct markers per subnet element; count how often each target is written
+    hits = [np.zeros(w.shape, dtype=np.float32) for w in Ws]
+    ones = [([np.ones_like(w) for w in Wl], bl) for Wl, bl in subs]
+    H = orc.blocks(perms, S)
+    for s in range(S):
+        for l in range(1, cfg.t + 1):
+            ridx = None if l == cfg.t else H[l - 1][s]
+            cidx = None if l == 1 else H[l - 2][s]
+            tmp = np.zeros_like(hits[l - 1])
+            orc.scatter(tmp, ridx, cidx, ones[s][0][l - 1])
+            hits[l - 1] += tmp
+    for l in range(1, cfg.t + 1):
+        assert hits[l - 1].max() == 1.0                              # no position written twice
+        unowned = int((hits[l - 1] == 0).sum())
+        middle = 1 < l < cfg.t
+        assert unowned == (dims[l] * dims[l - 1] * (S - 1) // S if middle else 0)
+    # after a merge of modified subnets the unowned entries keep their bits
+    W0 = [w.copy() for w in Ws]
+    mod = [([w + 1.0 for w in Wl], bl) for Wl, bl in subs]
+    orc.merge(Ws, bs, perms, S, mod)
+    for l in range(cfg.t):
+        un = hits[l] == 0
+        assert np.array_equal(Ws[l][un], W0[l][un])
+        assert np.array_equal(Ws[l][~un], W0[l][~un] + 1.0)
+
+
+def test_output_bias_merge_is_the_mean():
+    S, n = 4, 5
+    rng = np.random.default_rng(0)
+    b = rng.standard_normal((S, n)).astype(np.float32)
+    cfg = _cfg((3, 8, n), S)
+    Ws, bs = gen.make_weights(cfg)
+    perms = gen.make_perms(cfg)
+    subs = orc.partition(Ws, bs, perms, S)
+    subs = [(Wl, [bl[0], b[s]]) for s, (Wl, bl) in enumerate(subs)]
+    orc.merge(Ws, bs, perms, S, subs)
+    np.testing.assert_allclose(bs[-1], b.astype(np.float64).mean(axis=0), rtol=1e-6, atol=1e-7)
+    # identical copies come back exactly when S is a power of two
+    same = [(Wl, [bl[0], b[0]]) for Wl, bl in subs]
+    orc.merge(Ws, bs, perms, S, same)
+    assert np.array_equal(bs[-1], b[0])
