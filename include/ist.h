@@ -1,0 +1,153 @@
+/*
+ * ist.h - C ABI of the MI355X (gfx950) hot path of Independent Subnet Training.
+ *
+ * Paper: "Distributed Learning of Fully Connected Neural Networks using
+ * Independent Subnet Training" (IST).  One IST round is
+ *
+ *     ist_partition  ->  ist_subnet_steps (k local SGD steps)  ->  ist_merge
+ *
+ * with all S subnets resident on one GPU.  Notation follows the paper: layers
+ * 0..t, N_l neurons at layer l, W_l in R^{N_l x N_{l-1}} with f_l = W_l f_{l-1}
+ * (Appendix A), S = the paper's n sites, k = the paper's J local iterations.
+ *
+ * Conventions
+ *   - Every pointer marked [device] is GPU memory owned by the caller (for
+ *     instance a PyTorch tensor); the library never allocates or frees device
+ *     memory.  Pointers marked [host] are ordinary host memory read during the
+ *     call only.  Structs themselves are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return; results are ready when the stream
+ *     reaches that point.
+ *   - All functions return an ist_status (0 = IST_OK, < 0 = error), never throw
+ *     and never abort.  Argument errors are detected on the host before anything
+ *     is enqueued.  ist_last_error() gives a text for the last failure.
+ *   - Matrices are row-major.  Storage types: IST_F32 (IEEE binary32) or
+ *     IST_BF16 (bfloat16); accumulation is always binary32.
+ */
+#ifndef IST_H
+#define IST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    IST_OK = 0,
+    IST_EINVAL = -1,       /* null pointer, non-positive size, bad enum */
+    IST_ESHAPE = -2,       /* S does not divide a hidden width, B > max_B, ... */
+    IST_EPERM = -3,        /* a perm is not a permutation of 0..N_l-1 (checked mode) */
+    IST_ENOMEM = -4,       /* a bound buffer is too small */
+    IST_EHIP = -5,         /* a HIP runtime call failed */
+    IST_ESTATE = -6,       /* call order violated (steps/merge before partition, no bind) */
+    IST_EUNSUPPORTED = -7  /* valid request the library does not implement */
+} ist_status;
+
+typedef enum { IST_F32 = 0, IST_BF16 = 1 } ist_dtype;
+typedef enum { IST_DENSE = 0, IST_CSR = 1 } ist_input_kind;
+
+/* The full network and how it is split. [host] */
+typedef struct {
+    int32_t t;             /* number of weight matrices, >= 2 (at least one hidden layer) */
+    const int64_t *dims;   /* [host] N_0..N_t, t+1 entries; S must divide N_1..N_{t-1} */
+    int32_t S;             /* number of subnets, >= 1 */
+    int32_t dtype;         /* ist_dtype: storage of W, b, activations, inputs */
+    int32_t input;         /* ist_input_kind of the mini-batches */
+    int32_t has_bias;      /* 1: biases b_1..b_t exist, 0: none */
+} ist_model_desc;
+
+/* Full parameters, caller-owned. [host struct, device arrays] */
+typedef struct {
+    void *const *W;        /* [host] t pointers; W[l-1] -> [device] row-major [N_l][N_{l-1}] */
+    void *const *b;        /* [host] t pointers; b[l-1] -> [device] [N_l]; NULL if has_bias == 0 */
+} ist_params;
+
+/* Mini-batches for all S subnets and k steps: sample b of step j of subnet s is
+ * row  s*stride_s + j*stride_k + b.  Every (s, j) normally has its own batch;
+ * stride 0 reuses one.  [host struct, device arrays] */
+typedef struct {
+    const void *x;         /* dense: [device] rows of N_0 values in the model dtype */
+    const int32_t *rowptr; /* CSR: [device] row offsets, (max row index + 2) entries */
+    const int32_t *colidx; /* CSR: [device] column ids, ascending inside a row, < N_0 */
+    const void *vals;      /* CSR: [device] values in the model dtype */
+    int64_t nnz;           /* CSR: length of colidx / vals */
+    const int32_t *y;      /* [device] class id per row, 0 <= y < N_t */
+    int64_t stride_s;      /* rows between consecutive subnets */
+    int64_t stride_k;      /* rows between consecutive steps */
+    int32_t B;             /* mini-batch size, 1..max_B */
+} ist_batch;
+
+typedef struct ist_ctx ist_ctx;
+
+/* Creates the host-side plan for one network shape.  No device work.
+ * IST_ESHAPE if S does not divide a hidden width or max_B < 1. */
+ist_status ist_create(const ist_model_desc *desc, int32_t max_B, ist_ctx **out);
+ist_status ist_destroy(ist_ctx *ctx);
+
+/* Sizes of the two device buffers the caller must provide: `subnets` holds the
+ * packed parameters of all S subnets plus the neuron index tables (private
+ * layout), `workspace` holds activations, gradients and scratch for
+ * ist_subnet_steps.  Both must be 256-byte aligned. */
+ist_status ist_subnets_bytes(const ist_ctx *ctx, size_t *bytes);
+ist_status ist_workspace_bytes(const ist_ctx *ctx, size_t *bytes);
+ist_status ist_bind(ist_ctx *ctx, void *subnets /*[device]*/, size_t subnets_bytes,
+                    void *workspace /*[device]*/, size_t workspace_bytes);
+
+/* checked != 0: ist_partition synchronises the stream and returns IST_EPERM if a
+ * permutation is invalid.  Unchecked (default), an invalid permutation gives
+ * unspecified subnet contents but never an out-of-bounds access. */
+ist_status ist_set_checked(ist_ctx *ctx, int32_t checked);
+
+/*
+ * ist_partition - Section 2.1 "Constructing Subnets", Appendix A.
+ * perm[l-1] [device], l = 1..t-1, is a permutation of 0..N_l-1; subnet s owns
+ * the neurons H_l^s = perm_l[s*N_l/S .. (s+1)*N_l/S - 1] of hidden layer l, and
+ * all input and output neurons.  Copies W_l[H_l^s, H_{l-1}^s] and b_l[H_l^s]
+ * into the bound subnet buffer for every s (bit-exact copies; the output bias
+ * b_t is replicated).  `params` is only read.
+ */
+ist_status ist_partition(ist_ctx *ctx, const ist_params *params,
+                         const int32_t *const *perm /*[host] t-1 [device] pointers*/,
+                         void *stream);
+
+/*
+ * ist_subnet_steps - Section 2.1 "Training Subnets", Appendix B (local step
+ * w <- w - lr * grad).  Runs k steps of mini-batch SGD on each of the S subnets
+ * independently: forward through the narrow net (ReLU hidden units, no n^2
+ * factor, Section 2.2), mean softmax cross-entropy, back-propagation, in-place
+ * update of the subnet parameters.  Values are kept in the model dtype
+ * (round-to-nearest-even): W, b, hidden activations and activation gradients;
+ * logits, softmax, reductions and the update arithmetic are binary32.
+ * loss_out: [device] float [S][k], mean loss of each step before its update,
+ * or NULL.  May be called repeatedly between partition and merge.
+ */
+ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *batch, float lr, int32_t k,
+                            float *loss_out, void *stream);
+
+/*
+ * ist_merge - Section 2.1 "Training Subnets": subnet parameters are copied back
+ * into the full network; blocks are disjoint so nothing collides, and entries
+ * of W owned by no subnet keep their bits.  Hidden biases return to their
+ * neuron; b_t becomes the mean over subnets (binary32 sum in subnet order times
+ * 1/S, rounded to dtype).  Writes `params` in place; subnets stay valid.
+ */
+ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream);
+
+/* Canonical view of one subnet's layer l (1..t) for inspection and tests:
+ * dstW [device] row-major [rows][cols] with rows/cols in the order of the
+ * permutation block (H_l^s order), dstb [device] [rows] or NULL. */
+ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, void *dstb,
+                             void *stream);
+
+/* Rows and columns of subnet layer l as ist_subnet_export writes them. */
+ist_status ist_subnet_shape(const ist_ctx *ctx, int32_t l, int64_t *rows, int64_t *cols);
+
+const char *ist_last_error(const ist_ctx *ctx);
+const char *ist_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IST_H */

@@ -1,0 +1,410 @@
+// C ABI of the IST library: host-side plan, argument checks and kernel sequencing.
+// See include/ist.h for the contract of every entry point.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "ist_internal.h"
+
+namespace ist {
+hipError_t launch_perm_check(const int32_t *perm, const int32_t *invpos, int64_t N, int32_t *err,
+                             hipStream_t st);
+}
+
+using namespace ist;
+
+namespace {
+
+ist_status fail(ist_ctx *ctx, ist_status st, const std::string &msg)
+{
+    if (ctx) ctx->err = msg;
+    return st;
+}
+
+ist_status hip_fail(ist_ctx *ctx, hipError_t e, const char *where)
+{
+    return fail(ctx, IST_EHIP, std::string(where) + ": " + hipGetErrorString(e));
+}
+
+#define IST_HIP(call, where)                                   \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, where); \
+    } while (0)
+
+inline const int32_t *tbl(const ist_ctx *ctx, size_t off)
+{
+    return reinterpret_cast<const int32_t *>(ctx->subnets + off);
+}
+
+// Arguments of the block copy of layer l (1-based) between `params` and the subnet buffer.
+CopyArgs copy_args(const ist_ctx *ctx, int l, void *Wfull)
+{
+    const LayerPlan &L = ctx->layer[l - 1];
+    CopyArgs a{};
+    a.W = Wfull;
+    a.ld = L.N_in;
+    a.sub = ctx->subnets + L.off_W;
+    a.rows = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_sorted) : nullptr;
+    a.cols = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_sorted) : nullptr;
+    a.slotc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_slot) : nullptr;
+    a.nr = L.R;
+    a.nc = L.C;
+    a.N_out = L.N_out;
+    a.N_in = L.N_in;
+    a.G = ctx->S;
+    a.esz = ctx->esz();
+    a.transposed = L.transposed;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ist_version(void) { return "ist-gfx950 0.1"; }
+
+const char *ist_last_error(const ist_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
+{
+    if (!d || !out || !d->dims) return IST_EINVAL;
+    *out = nullptr;
+    if (d->t < 2 || d->S < 1 || (d->dtype != IST_F32 && d->dtype != IST_BF16) ||
+        (d->input != IST_DENSE && d->input != IST_CSR) || (d->has_bias != 0 && d->has_bias != 1))
+        return IST_EINVAL;
+    if (max_B < 1) return IST_ESHAPE;
+    for (int l = 0; l <= d->t; ++l) {
+        if (d->dims[l] < 1 || d->dims[l] > 0x7fffffffLL) return IST_ESHAPE;
+        if (l > 0 && l < d->t && d->dims[l] % d->S != 0) return IST_ESHAPE;
+    }
+    ist_ctx *ctx = new (std::nothrow) ist_ctx();
+    if (!ctx) return IST_ENOMEM;
+    ctx->t = d->t; ctx->S = d->S; ctx->dtype = d->dtype; ctx->input = d->input;
+    ctx->has_bias = d->has_bias; ctx->max_B = max_B;
+    ctx->dims.assign(d->dims, d->dims + d->t + 1);
+    const int t = d->t, S = d->S, e = ctx->esz();
+
+    // ---- subnet buffer: index tables, then per-layer blocks and biases ----
+    size_t off = 0;
+    ctx->hidden.resize(t - 1);
+    for (int l = 1; l < t; ++l) {
+        HiddenPlan &h = ctx->hidden[l - 1];
+        h.N = ctx->dims[l];
+        h.w = h.N / S;
+        h.off_sorted = off; off = align_up(off + sizeof(int32_t) * h.N);
+        h.off_slot = off;   off = align_up(off + sizeof(int32_t) * h.N);
+        h.off_p2q = off;    off = align_up(off + sizeof(int32_t) * h.N);
+    }
+    const size_t tables_end = off;
+    ctx->layer.resize(t);
+    for (int l = 1; l <= t; ++l) {
+        LayerPlan &L = ctx->layer[l - 1];
+        L.N_out = ctx->dims[l]; L.N_in = ctx->dims[l - 1];
+        L.row_part = l < t; L.col_part = l > 1;
+        L.R = L.row_part ? L.N_out / S : L.N_out;
+        L.C = L.col_part ? L.N_in / S : L.N_in;
+        L.transposed = (l == 1 && d->input == IST_CSR);
+        L.off_W = off; off = align_up(off + (size_t)S * L.R * L.C * e);
+        L.off_b = off; off = align_up(off + (size_t)S * L.R * e);
+    }
+    ctx->subnets_bytes = off;
+    (void)tables_end;
+
+    // ---- workspace ----
+    size_t w = 0;
+    for (int l = 1; l < t; ++l) {
+        ctx->hidden[l - 1].off_invpos = w;
+        w = align_up(w + sizeof(int32_t) * ctx->hidden[l - 1].N);
+    }
+    for (int l = 1; l <= t; ++l) {
+        LayerPlan &L = ctx->layer[l - 1];
+        size_t act_e = (l == t) ? sizeof(float) : (size_t)e;
+        L.off_act = w; w = align_up(w + (size_t)S * max_B * L.R * act_e);
+        L.off_dz = w;  w = align_up(w + (size_t)S * max_B * L.R * e);
+    }
+    ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)S * max_B);
+    ctx->off_bitmap = w;
+    if (d->input == IST_CSR)
+        w = align_up(w + sizeof(uint32_t) * (size_t)S * ctx->dims[0] * ((max_B + 31) / 32));
+    ctx->off_err = w; w = align_up(w + sizeof(int32_t));
+    ctx->workspace_bytes = w;
+    *out = ctx;
+    return IST_OK;
+}
+
+ist_status ist_destroy(ist_ctx *ctx)
+{
+    delete ctx;
+    return IST_OK;
+}
+
+ist_status ist_subnets_bytes(const ist_ctx *ctx, size_t *bytes)
+{
+    if (!ctx || !bytes) return IST_EINVAL;
+    *bytes = ctx->subnets_bytes;
+    return IST_OK;
+}
+
+ist_status ist_workspace_bytes(const ist_ctx *ctx, size_t *bytes)
+{
+    if (!ctx || !bytes) return IST_EINVAL;
+    *bytes = ctx->workspace_bytes;
+    return IST_OK;
+}
+
+ist_status ist_bind(ist_ctx *ctx, void *subnets, size_t sb, void *workspace, size_t wb)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!subnets || !workspace) return fail(ctx, IST_EINVAL, "ist_bind: null buffer");
+    if (sb < ctx->subnets_bytes || wb < ctx->workspace_bytes)
+        return fail(ctx, IST_ENOMEM, "ist_bind: buffer smaller than ist_*_bytes reports");
+    if (reinterpret_cast<uintptr_t>(subnets) % kAlign || reinterpret_cast<uintptr_t>(workspace) % kAlign)
+        return fail(ctx, IST_EINVAL, "ist_bind: buffers must be 256-byte aligned");
+    ctx->subnets = static_cast<char *>(subnets);
+    ctx->workspace = static_cast<char *>(workspace);
+    ctx->partitioned = false;
+    // Index tables start as zeros so that they hold in-range values at all times,
+    // also after a partition with an invalid permutation.
+    const size_t tables = ctx->layer[0].off_W;
+    IST_HIP(hipMemset(ctx->subnets, 0, tables), "ist_bind: clear tables");
+    IST_HIP(hipMemset(ctx->workspace, 0, ctx->layer[0].off_act), "ist_bind: clear scratch tables");
+    IST_HIP(hipMemset(ctx->workspace + ctx->off_err, 0, sizeof(int32_t)), "ist_bind: clear flag");
+    ctx->bound = true;
+    return IST_OK;
+}
+
+ist_status ist_set_checked(ist_ctx *ctx, int32_t checked)
+{
+    if (!ctx) return IST_EINVAL;
+    ctx->checked = checked ? 1 : 0;
+    return IST_OK;
+}
+
+ist_status ist_subnet_shape(const ist_ctx *ctx, int32_t l, int64_t *rows, int64_t *cols)
+{
+    if (!ctx || !rows || !cols || l < 1 || l > ctx->t) return IST_EINVAL;
+    *rows = ctx->layer[l - 1].R;
+    *cols = ctx->layer[l - 1].C;
+    return IST_OK;
+}
+
+static ist_status check_params(ist_ctx *ctx, const ist_params *p, const char *who)
+{
+    if (!p || !p->W) return fail(ctx, IST_EINVAL, std::string(who) + ": null params");
+    if (ctx->has_bias && !p->b) return fail(ctx, IST_EINVAL, std::string(who) + ": null bias list");
+    for (int l = 1; l <= ctx->t; ++l) {
+        if (!p->W[l - 1]) return fail(ctx, IST_EINVAL, std::string(who) + ": null W_l");
+        if (ctx->has_bias && !p->b[l - 1]) return fail(ctx, IST_EINVAL, std::string(who) + ": null b_l");
+        if (reinterpret_cast<uintptr_t>(p->W[l - 1]) % ctx->esz())
+            return fail(ctx, IST_EINVAL, std::string(who) + ": misaligned W_l");
+    }
+    return IST_OK;
+}
+
+ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *const *perm,
+                         void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound) return fail(ctx, IST_ESTATE, "ist_partition: no buffers bound");
+    ist_status ps = check_params(ctx, params, "ist_partition");
+    if (ps != IST_OK) return ps;
+    if (!perm) return fail(ctx, IST_EINVAL, "ist_partition: null perm list");
+    for (int l = 1; l < ctx->t; ++l)
+        if (!perm[l - 1]) return fail(ctx, IST_EINVAL, "ist_partition: null perm");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int t = ctx->t, S = ctx->S, e = ctx->esz();
+    ctx->partitioned = false;
+
+    if (ctx->checked) {
+        IST_HIP(hipMemsetAsync(ctx->errflag(), 0, sizeof(int32_t), st), "clear flag");
+        for (int l = 1; l < t; ++l)
+            IST_HIP(hipMemsetAsync(ctx->workspace + ctx->hidden[l - 1].off_invpos, 0xff,
+                                   sizeof(int32_t) * ctx->hidden[l - 1].N, st), "clear invpos");
+    }
+    for (int l = 1; l < t; ++l) {
+        const HiddenPlan &h = ctx->hidden[l - 1];
+        int32_t *invpos = reinterpret_cast<int32_t *>(ctx->workspace + h.off_invpos);
+        IST_HIP(launch_perm_tables(perm[l - 1], h.N, S, invpos,
+                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_sorted),
+                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_slot),
+                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_p2q),
+                                   ctx->errflag(), st), "perm tables");
+        if (ctx->checked)
+            IST_HIP(launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");
+    }
+    if (ctx->checked) {
+        int32_t flag = 0;
+        IST_HIP(hipMemcpyAsync(&flag, ctx->errflag(), sizeof(flag), hipMemcpyDeviceToHost, st), "read flag");
+        IST_HIP(hipStreamSynchronize(st), "sync");
+        if (flag) return fail(ctx, IST_EPERM, "ist_partition: perm is not a permutation of 0..N_l-1");
+    }
+
+    for (int l = 1; l <= t; ++l) {
+        const LayerPlan &L = ctx->layer[l - 1];
+        CopyArgs a = copy_args(ctx, l, params->W[l - 1]);
+        IST_HIP(launch_partition_copy(a, st), "partition copy");
+        if (ctx->has_bias) {
+            if (l < t) {
+                CopyArgs b{};
+                b.W = params->b[l - 1]; b.ld = 1; b.sub = ctx->subnets + L.off_b;
+                b.rows = a.rows; b.cols = nullptr; b.nr = L.R; b.nc = 1; b.G = S; b.esz = e;
+                b.N_out = L.N_out; b.N_in = 1; b.transposed = false;
+                IST_HIP(launch_partition_copy(b, st), "partition bias");
+            } else {
+                IST_HIP(launch_bias_replicate(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, e, st),
+                        "replicate output bias");
+            }
+        }
+    }
+    ctx->partitioned = true;
+    return IST_OK;
+}
+
+ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound || !ctx->partitioned) return fail(ctx, IST_ESTATE, "ist_merge: call ist_partition first");
+    ist_status ps = check_params(ctx, params, "ist_merge");
+    if (ps != IST_OK) return ps;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int t = ctx->t, S = ctx->S, e = ctx->esz();
+    for (int l = 1; l <= t; ++l) {
+        const LayerPlan &L = ctx->layer[l - 1];
+        CopyArgs a = copy_args(ctx, l, params->W[l - 1]);
+        IST_HIP(launch_merge_copy(a, st), "merge copy");
+        if (ctx->has_bias) {
+            if (l < t) {
+                CopyArgs b{};
+                b.W = params->b[l - 1]; b.ld = 1; b.sub = ctx->subnets + L.off_b;
+                b.rows = a.rows; b.cols = nullptr; b.nr = L.R; b.nc = 1; b.G = S; b.esz = e;
+                b.N_out = L.N_out; b.N_in = 1; b.transposed = false;
+                IST_HIP(launch_merge_copy(b, st), "merge bias");
+            } else {
+                IST_HIP(launch_bias_mean(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, ctx->dtype, st),
+                        "mean output bias");
+            }
+        }
+    }
+    return IST_OK;
+}
+
+ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, void *dstb, void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound || !ctx->partitioned) return fail(ctx, IST_ESTATE, "ist_subnet_export: call ist_partition first");
+    if (s < 0 || s >= ctx->S || l < 1 || l > ctx->t || !dstW) return fail(ctx, IST_EINVAL, "ist_subnet_export: bad argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const LayerPlan &L = ctx->layer[l - 1];
+    const int e = ctx->esz();
+    const int32_t *pr = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_p2q) : nullptr;
+    const int32_t *pc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_p2q) : nullptr;
+    const char *blk = ctx->subnets + L.off_W + (size_t)s * L.R * L.C * e;
+    IST_HIP(launch_export(blk, dstW, L.R, L.C, pr, (int64_t)s * L.R, pc, (int64_t)s * L.C, L.transposed, e, st),
+            "export W");
+    if (dstb) {
+        if (!ctx->has_bias) return fail(ctx, IST_EINVAL, "ist_subnet_export: model has no bias");
+        const char *bb = ctx->subnets + L.off_b + (size_t)s * L.R * e;
+        IST_HIP(launch_export(bb, dstb, L.R, 1, pr, (int64_t)s * L.R, nullptr, 0, false, e, st), "export b");
+    }
+    return IST_OK;
+}
+
+ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t k, float *loss_out,
+                            void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound || !ctx->partitioned) return fail(ctx, IST_ESTATE, "ist_subnet_steps: call ist_partition first");
+    if (!bt || !bt->y) return fail(ctx, IST_EINVAL, "ist_subnet_steps: null batch");
+    if (k < 0) return fail(ctx, IST_EINVAL, "ist_subnet_steps: k < 0");
+    if (bt->B < 1 || bt->B > ctx->max_B) return fail(ctx, IST_ESHAPE, "ist_subnet_steps: B outside 1..max_B");
+    if (bt->stride_s < 0 || bt->stride_k < 0) return fail(ctx, IST_EINVAL, "ist_subnet_steps: negative stride");
+    const bool csr = ctx->input == IST_CSR;
+    if (csr) {
+        if (!bt->rowptr || !bt->colidx || !bt->vals || bt->nnz < 0)
+            return fail(ctx, IST_EINVAL, "ist_subnet_steps: incomplete CSR batch");
+    } else if (!bt->x) {
+        return fail(ctx, IST_EINVAL, "ist_subnet_steps: null x");
+    }
+    if (!(lr == lr)) return fail(ctx, IST_EINVAL, "ist_subnet_steps: lr is NaN");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int t = ctx->t, S = ctx->S, e = ctx->esz(), B = bt->B, dt = ctx->dtype;
+    char *ws = ctx->workspace, *sb = ctx->subnets;
+    float *rowloss = reinterpret_cast<float *>(ws + ctx->off_rowloss);
+
+    for (int j = 0; j < k; ++j) {
+        const int64_t row0 = (int64_t)j * bt->stride_k;
+        // ---------------- forward ----------------
+        for (int l = 1; l <= t; ++l) {
+            const LayerPlan &L = ctx->layer[l - 1];
+            const void *bias = ctx->has_bias ? sb + L.off_b : nullptr;
+            if (l == 1 && csr) {
+                CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R};
+                IST_HIP(launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act, dt, st), "csr forward");
+                continue;
+            }
+            GemmArgs a{};
+            if (l == 1) {
+                a.A = static_cast<const char *>(bt->x) + (size_t)row0 * L.C * e;
+                a.gA = bt->stride_s * L.C;
+            } else {
+                a.A = ws + ctx->layer[l - 2].off_act;
+                a.gA = (int64_t)B * L.C;
+            }
+            a.sam = L.C; a.sak = 1;
+            a.B = sb + L.off_W; a.sbn = L.C; a.sbk = 1; a.gB = L.R * L.C;
+            a.C = ws + L.off_act; a.ldc = L.R; a.gC = (int64_t)B * L.R;
+            a.M = B; a.N = (int32_t)L.R; a.K = (int32_t)L.C; a.G = S;
+            a.bias = bias; a.gBias = L.R;
+            IST_HIP(launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
+        }
+        // ---------------- loss and dz_t ----------------
+        {
+            const LayerPlan &L = ctx->layer[t - 1];
+            IST_HIP(launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
+                                        bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, dt, st),
+                    "softmax cross-entropy");
+            if (loss_out) IST_HIP(launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
+        }
+        // ---------------- backward + update, top layer first ----------------
+        for (int l = t; l >= 1; --l) {
+            const LayerPlan &L = ctx->layer[l - 1];
+            if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by h_{l-1} > 0, old W_l
+                const LayerPlan &P = ctx->layer[l - 2];
+                GemmArgs a{};
+                a.A = ws + L.off_dz; a.sam = L.R; a.sak = 1; a.gA = (int64_t)B * L.R;
+                a.B = sb + L.off_W; a.sbn = 1; a.sbk = L.C; a.gB = L.R * L.C;
+                a.C = ws + P.off_dz; a.ldc = L.C; a.gC = (int64_t)B * L.C;
+                a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
+                a.mask = ws + P.off_act; a.ldm = L.C; a.gMask = (int64_t)B * L.C;
+                IST_HIP(launch_gemm(dt, EPI_BWD_DATA, a, st), "backward-data gemm");
+            }
+            if (l == 1 && csr) {
+                CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R};
+                IST_HIP(launch_csr_update(c, sb + L.off_W, ws + L.off_dz,
+                                          reinterpret_cast<uint32_t *>(ws + ctx->off_bitmap), lr, dt, st),
+                        "csr update");
+            } else {       // W_l <- W_l - lr * dz_l^T h_{l-1}
+                GemmArgs a{};
+                a.A = ws + L.off_dz; a.sam = 1; a.sak = L.R; a.gA = (int64_t)B * L.R;
+                if (l == 1) {
+                    a.B = static_cast<const char *>(bt->x) + (size_t)row0 * L.C * e;
+                    a.gB = bt->stride_s * L.C;
+                } else {
+                    a.B = ws + ctx->layer[l - 2].off_act;
+                    a.gB = (int64_t)B * L.C;
+                }
+                a.sbn = 1; a.sbk = L.C;
+                a.C = sb + L.off_W; a.ldc = L.C; a.gC = L.R * L.C;
+                a.M = (int32_t)L.R; a.N = (int32_t)L.C; a.K = B; a.G = S;
+                a.lr = lr;
+                IST_HIP(launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
+            }
+            if (ctx->has_bias)
+                IST_HIP(launch_bias_update(sb + L.off_b, ws + L.off_dz, S, B, L.R, lr, dt, st), "bias update");
+        }
+    }
+    return IST_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,159 @@
+// Sparse-input first layer (the extreme-classification workload of Section 3.1:
+// 135,909 sparse features).  The subnet's W_1 block is stored transposed,
+// Wt[g][c][q] = W_1[H_1^g[q]][c], so that one non-zero of a sample touches one
+// contiguous row of w = N_1/S values.
+//
+//   forward : h_1[b][q] = ReLU(sum_{(c,v) in row b} v * Wt[c][q] + b_1[q])
+//   update  : Wt[c][:] <- Wt[c][:] - lr * sum_{b : c in row b} x[b][c] * dz_1[b][:]
+//             for the columns c that occur in the batch (all others have a zero
+//             gradient).  The sum over b runs in ascending b so the result does not
+//             depend on scheduling: a bitmap (one bit per sample) per column is
+//             built with integer atomics, then one wavefront owns one column.
+#include "ist_internal.h"
+
+namespace ist {
+
+template <typename D>
+__global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D::T *__restrict__ Wt,
+                                                     const typename D::T *__restrict__ bias,
+                                                     typename D::T *__restrict__ h)
+{
+    using T = typename D::T;
+    const int g = blockIdx.z, b = blockIdx.y;
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= c.w) return;
+    const int64_t row = c.row0 + (int64_t)g * c.stride_g + b;
+    int64_t p0 = c.rowptr[row], p1 = c.rowptr[row + 1];
+    p0 = p0 < 0 ? 0 : p0;
+    p1 = p1 > c.nnz ? c.nnz : p1;
+    const T *Wg = Wt + (int64_t)g * c.N0 * c.w;
+    const T *vals = static_cast<const T *>(c.vals);
+    float acc = 0.0f;
+    for (int64_t p = p0; p < p1; ++p) {
+        int32_t col = c.colidx[p];
+        if (col < 0 || col >= c.N0) continue;
+        acc = fmaf(D::up(vals[p]), D::ld(Wg + (int64_t)col * c.w + q), acc);
+    }
+    if (bias) acc += D::ld(bias + (int64_t)g * c.w + q);
+    h[((int64_t)g * c.B + b) * c.w + q] = D::cvt(acc > 0.0f ? acc : 0.0f);
+}
+
+__global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// bitmap[g][col][b >> 5] |= 1 << (b & 31) for every non-zero (b, col) of group g
+__global__ __launch_bounds__(256) void k_csr_mark(CsrArgs c, uint32_t *__restrict__ bitmap, int words)
+{
+    const int g = blockIdx.y, b = blockIdx.x;
+    const int64_t row = c.row0 + (int64_t)g * c.stride_g + b;
+    int64_t p0 = c.rowptr[row], p1 = c.rowptr[row + 1];
+    p0 = p0 < 0 ? 0 : p0;
+    p1 = p1 > c.nnz ? c.nnz : p1;
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += blockDim.x) {
+        int32_t col = c.colidx[p];
+        if (col < 0 || col >= c.N0) continue;
+        atomicOr(bitmap + ((int64_t)g * c.N0 + col) * words + (b >> 5), 1u << (b & 31));
+    }
+}
+
+// One wavefront per (group, column).  Lanes look up, in parallel, the value
+// x[b][col] of up to 64 samples (binary search in the sample's ascending column
+// list), then the wave accumulates dz rows in ascending b.
+template <typename D>
+__global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__restrict__ Wt,
+                                                    const typename D::T *__restrict__ dz,
+                                                    const uint32_t *__restrict__ bitmap, int words,
+                                                    float lr)
+{
+    using T = typename D::T;
+    const int lane = threadIdx.x & 63;
+    const int64_t wid = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (wid >= (int64_t)c.G * c.N0) return;
+    const int g = (int)(wid / c.N0);
+    const int32_t col = (int32_t)(wid % c.N0);
+    const uint32_t *bm = bitmap + wid * words;
+    bool any = false;
+    for (int i = lane; i < words; i += 64) any |= (bm[i] != 0u);
+    if (__ballot(any) == 0ull) return;
+
+    const T *vals = static_cast<const T *>(c.vals);
+    T *wrow = Wt + ((int64_t)g * c.N0 + col) * c.w;
+    const T *dzg = dz + (int64_t)g * c.B * c.w;
+    for (int64_t q0 = 0; q0 < c.w; q0 += 256) {          // 4 outputs per lane per pass
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int b0 = 0; b0 < c.B; b0 += 64) {
+            const int b = b0 + lane;
+            bool has = (b < c.B) && ((bm[b >> 5] >> (b & 31)) & 1u);
+            float v = 0.0f;
+            if (has) {
+                const int64_t row = c.row0 + (int64_t)g * c.stride_g + b;
+                int64_t lo = c.rowptr[row], hi = c.rowptr[row + 1];
+                lo = lo < 0 ? 0 : lo;
+                hi = hi > c.nnz ? c.nnz : hi;
+                while (lo < hi) {                         // first position with colidx >= col
+                    int64_t mid = (lo + hi) >> 1;
+                    if (c.colidx[mid] < col) lo = mid + 1; else hi = mid;
+                }
+                // duplicates of a column inside one row are summed
+                int64_t end = c.rowptr[row + 1] > c.nnz ? c.nnz : c.rowptr[row + 1];
+                for (int64_t p = lo; p < end && c.colidx[p] == col; ++p) v += D::up(vals[p]);
+            }
+            unsigned long long m = __ballot(has);
+            while (m) {
+                const int src = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                const float xv = __shfl(v, src);
+                const T *dr = dzg + (int64_t)(b0 + src) * c.w + q0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int64_t q = (int64_t)i * 64 + lane;
+                    if (q0 + q < c.w) acc[i] = fmaf(xv, D::ld(dr + q), acc[i]);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int64_t q = q0 + (int64_t)i * 64 + lane;
+            if (q < c.w) wrow[q] = D::cvt(D::up(wrow[q]) - lr * acc[i]);
+        }
+    }
+}
+
+hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, int dtype,
+                              hipStream_t st)
+{
+    int th = c.w >= 256 ? 256 : (c.w > 64 ? 128 : 64);
+    dim3 grid((unsigned)((c.w + th - 1) / th), (unsigned)c.B, (unsigned)c.G);
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL(k_csr_forward<BF16>, grid, dim3(th), 0, st, c, (const uint16_t *)Wt,
+                           (const uint16_t *)bias, (uint16_t *)h);
+    else
+        hipLaunchKernelGGL(k_csr_forward<F32>, grid, dim3(th), 0, st, c, (const float *)Wt,
+                           (const float *)bias, (float *)h);
+    return hipGetLastError();
+}
+
+hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_t *bitmap, float lr,
+                             int dtype, hipStream_t st)
+{
+    const int words = (c.B + 31) / 32;
+    const int64_t nwords = (int64_t)c.G * c.N0 * words;
+    hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, st, bitmap, nwords, 0u);
+    hipLaunchKernelGGL(k_csr_mark, dim3((unsigned)c.B, (unsigned)c.G), dim3(256), 0, st, c, bitmap,
+                       words);
+    const int64_t waves = (int64_t)c.G * c.N0;
+    dim3 grid((unsigned)((waves + 3) / 4));
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL(k_csr_update<BF16>, grid, dim3(256), 0, st, c, (uint16_t *)Wt,
+                           (const uint16_t *)dz, bitmap, words, lr);
+    else
+        hipLaunchKernelGGL(k_csr_update<F32>, grid, dim3(256), 0, st, c, (float *)Wt,
+                           (const float *)dz, bitmap, words, lr);
+    return hipGetLastError();
+}
+
+}  // namespace ist

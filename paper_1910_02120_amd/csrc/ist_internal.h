@@ -1,0 +1,148 @@
+// Internal declarations of the IST library (host plan + kernel launchers).
+// gfx950 only.  Nothing here is shared with the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "ist.h"
+
+namespace ist {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// ----------------------------------------------------------------- storage types
+struct F32 {
+    using T = float;
+    static constexpr int kBytes = 4;
+    __device__ static inline float ld(const T *p) { return *p; }
+    __device__ static inline T cvt(float v) { return v; }
+    __device__ static inline float up(T v) { return v; }
+};
+
+__device__ inline float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ inline uint16_t f32_to_bf16(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+struct BF16 {
+    using T = uint16_t;
+    static constexpr int kBytes = 2;
+    __device__ static inline float ld(const T *p) { return bf16_to_f32(*p); }
+    __device__ static inline T cvt(float v) { return f32_to_bf16(v); }
+    __device__ static inline float up(T v) { return bf16_to_f32(v); }
+};
+
+// ----------------------------------------------------------------- host plan
+struct LayerPlan {           // weight matrix l = 1..t
+    int64_t N_out = 0, N_in = 0;   // full sizes N_l, N_{l-1}
+    int64_t R = 0, C = 0;          // rows/cols held by one subnet
+    bool row_part = false;         // rows follow the blocks of hidden layer l
+    bool col_part = false;         // cols follow the blocks of hidden layer l-1
+    bool transposed = false;       // stored [S][C][R] (sparse-input first layer)
+    size_t off_W = 0, off_b = 0;   // byte offsets into the subnet buffer
+    size_t off_act = 0;            // workspace: h_l [S][maxB][R] dtype (l < t), logits fp32 (l == t)
+    size_t off_dz = 0;             // workspace: dz_l [S][maxB][R] dtype
+};
+
+struct HiddenPlan {          // hidden layer l = 1..t-1
+    int64_t N = 0, w = 0;
+    size_t off_sorted = 0;   // subnet buffer: int32 [N]  neuron id at sorted position P
+    size_t off_slot = 0;     // subnet buffer: int32 [N]  sorted position of neuron id
+    size_t off_p2q = 0;      // subnet buffer: int32 [N]  sorted position of perm position p
+    size_t off_invpos = 0;   // workspace:     int32 [N]  perm position of neuron id
+};
+
+}  // namespace ist
+
+struct ist_ctx {
+    int32_t t = 0, S = 0, dtype = 0, input = 0, has_bias = 0, max_B = 0;
+    std::vector<int64_t> dims;
+    std::vector<ist::LayerPlan> layer;    // index l-1
+    std::vector<ist::HiddenPlan> hidden;  // index l-1, l = 1..t-1
+    size_t subnets_bytes = 0, workspace_bytes = 0;
+    size_t off_rowloss = 0, off_bitmap = 0, off_err = 0;  // workspace
+    char *subnets = nullptr;
+    char *workspace = nullptr;
+    bool bound = false, partitioned = false;
+    int32_t checked = 0;
+    std::string err;
+
+    int esz() const { return dtype == IST_BF16 ? 2 : 4; }
+    int32_t *errflag() const { return reinterpret_cast<int32_t *>(workspace + off_err); }
+};
+
+namespace ist {
+
+// ----------------------------------------------------------------- partition / merge
+hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
+                              int32_t *sorted, int32_t *slot, int32_t *p2q, int32_t *err,
+                              hipStream_t st);
+
+// out[g][i][j] = W[rows ? rows[g*nr+i] : i][cols ? cols[g*nc+j] : j]  (or the
+// reverse copy when scatter is set); transposed: the subnet block is [nc][nr].
+struct CopyArgs {
+    void *W;                 // full matrix, row-major, ld = N_in
+    int64_t ld;
+    void *sub;               // packed blocks [G][nr][nc] (or [G][nc][nr])
+    const int32_t *rows;     // sorted neuron ids of the row layer, or null
+    const int32_t *cols;     // sorted neuron ids of the col layer, or null
+    const int32_t *slotc;    // sorted position of each col-layer neuron, or null
+    int64_t nr, nc;          // rows/cols per subnet block
+    int64_t N_out, N_in;     // full sizes
+    int32_t G;
+    int esz;
+    bool transposed;
+};
+hipError_t launch_partition_copy(const CopyArgs &a, hipStream_t st);
+hipError_t launch_merge_copy(const CopyArgs &a, hipStream_t st);
+hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G, int esz,
+                                 hipStream_t st);
+hipError_t launch_bias_mean(void *b, const void *sub, int64_t n, int32_t G, int dtype,
+                            hipStream_t st);
+hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc,
+                         const int32_t *p2q_r, int64_t base_r, const int32_t *p2q_c,
+                         int64_t base_c, bool transposed, int esz, hipStream_t st);
+
+// ----------------------------------------------------------------- training
+enum Epilogue { EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3 };
+
+// C[g][m][n] (+)= sum_k A_g(m,k) * B_g(n,k), element (m,k) of A at A + g*gA + m*sam + k*sak.
+struct GemmArgs {
+    const void *A; int64_t sam, sak, gA;
+    const void *B; int64_t sbn, sbk, gB;
+    void *C; int64_t ldc, gC;
+    int32_t M, N, K, G;
+    const void *bias; int64_t gBias;          // EPI_FWD_*: bias[n] (may be null)
+    const void *mask; int64_t ldm, gMask;     // EPI_BWD_DATA: keep where mask[m][n] > 0
+    float lr;                                 // EPI_UPDATE: C = C - lr * acc
+};
+hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+
+hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
+                               void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
+                               int dtype, hipStream_t st);
+hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
+                              int32_t G, int32_t B, hipStream_t st);
+hipError_t launch_bias_update(void *bias, const void *dz, int32_t G, int32_t B, int64_t R,
+                              float lr, int dtype, hipStream_t st);
+
+// sparse-input first layer (weights stored [G][N0][w])
+struct CsrArgs {
+    const int32_t *rowptr, *colidx; const void *vals; int64_t nnz;
+    int64_t row0, stride_g;   // sample b of group g is CSR row row0 + g*stride_g + b
+    int32_t G, B; int64_t N0, w;
+};
+hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h,
+                              int dtype, hipStream_t st);
+hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_t *bitmap,
+                             float lr, int dtype, hipStream_t st);
+
+}  // namespace ist

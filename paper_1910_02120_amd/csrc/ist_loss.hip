@@ -1,0 +1,139 @@
+// Softmax cross-entropy (forward + gradient), loss reduction and bias update of
+// the local SGD step (Section 2.1 "Training Subnets"; loss of equation (1) taken
+// as the mean softmax cross-entropy over the mini-batch).
+#include "ist_internal.h"
+
+namespace ist {
+
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+template <int NT>
+__device__ inline float block_reduce(float v, float *sh, bool is_max)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = is_max ? wave_max(v) : wave_sum(v);
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    float r = sh[0];
+    for (int i = 1; i < NT / 64; ++i) r = is_max ? fmaxf(r, sh[i]) : r + sh[i];
+    return r;
+}
+
+// One workgroup per (subnet g, sample b): dz = (softmax(z) - onehot(y)) / B in the
+// storage dtype, rowloss = logsumexp(z) - z[y].
+template <typename D, int NT>
+__global__ __launch_bounds__(NT) void k_softmax_xent(const float *__restrict__ logits,
+                                                     const int32_t *__restrict__ y,
+                                                     int64_t y_stride_g,
+                                                     typename D::T *__restrict__ dz,
+                                                     float *__restrict__ rowloss, int32_t B,
+                                                     int64_t Cn)
+{
+    __shared__ float sh[NT / 64];
+    const int g = blockIdx.y, b = blockIdx.x;
+    const float *z = logits + ((int64_t)g * B + b) * Cn;
+    typename D::T *out = dz + ((int64_t)g * B + b) * Cn;
+    float mx = -INFINITY;
+    for (int64_t c = threadIdx.x; c < Cn; c += NT) mx = fmaxf(mx, z[c]);
+    mx = block_reduce<NT>(mx, sh, true);
+    float se = 0.0f;
+    for (int64_t c = threadIdx.x; c < Cn; c += NT) se += __expf(z[c] - mx);
+    se = block_reduce<NT>(se, sh, false);
+    const int32_t label = y[(int64_t)g * y_stride_g + b];
+    const float inv = 1.0f / se, invB = 1.0f / (float)B;
+    for (int64_t c = threadIdx.x; c < Cn; c += NT) {
+        float p = __expf(z[c] - mx) * inv;
+        if (c == label) p -= 1.0f;
+        out[c] = D::cvt(p * invB);
+    }
+    if (threadIdx.x == 0) {
+        float zl = (label >= 0 && label < Cn) ? z[label] : mx;
+        rowloss[(int64_t)g * B + b] = __logf(se) + mx - zl;
+    }
+}
+
+hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g, void *dz,
+                               float *rowloss, int32_t G, int32_t B, int64_t Cn, int dtype,
+                               hipStream_t st)
+{
+    dim3 grid((unsigned)B, (unsigned)G);
+    if (Cn <= 256) {
+        if (dtype == IST_BF16)
+            hipLaunchKernelGGL((k_softmax_xent<BF16, 64>), grid, dim3(64), 0, st, logits, y, y_stride_g,
+                               (uint16_t *)dz, rowloss, B, Cn);
+        else
+            hipLaunchKernelGGL((k_softmax_xent<F32, 64>), grid, dim3(64), 0, st, logits, y, y_stride_g,
+                               (float *)dz, rowloss, B, Cn);
+    } else {
+        if (dtype == IST_BF16)
+            hipLaunchKernelGGL((k_softmax_xent<BF16, 1024>), grid, dim3(1024), 0, st, logits, y,
+                               y_stride_g, (uint16_t *)dz, rowloss, B, Cn);
+        else
+            hipLaunchKernelGGL((k_softmax_xent<F32, 1024>), grid, dim3(1024), 0, st, logits, y,
+                               y_stride_g, (float *)dz, rowloss, B, Cn);
+    }
+    return hipGetLastError();
+}
+
+// loss_out[g * out_stride_g] = mean_b rowloss[g][b]; one wave per subnet, fixed order.
+__global__ __launch_bounds__(64) void k_loss_reduce(const float *__restrict__ rowloss,
+                                                    float *__restrict__ loss_out,
+                                                    int64_t out_stride_g, int32_t B)
+{
+    const int g = blockIdx.x;
+    float acc = 0.0f;
+    for (int b = threadIdx.x; b < B; b += 64) acc += rowloss[(int64_t)g * B + b];
+    acc = wave_sum(acc);
+    if (threadIdx.x == 0) loss_out[(int64_t)g * out_stride_g] = acc / (float)B;
+}
+
+hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g, int32_t G,
+                              int32_t B, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_loss_reduce, dim3((unsigned)G), dim3(64), 0, st, rowloss, loss_out,
+                       out_stride_g, B);
+    return hipGetLastError();
+}
+
+// b[g][r] <- b[g][r] - lr * sum_b dz[g][b][r]
+template <typename D>
+__global__ __launch_bounds__(256) void k_bias_update(typename D::T *__restrict__ bias,
+                                                     const typename D::T *__restrict__ dz,
+                                                     int32_t B, int64_t R, float lr)
+{
+    const int g = blockIdx.y;
+    int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= R) return;
+    const typename D::T *p = dz + (int64_t)g * B * R + r;
+    float acc = 0.0f;
+    for (int b = 0; b < B; ++b) acc += D::ld(p + (int64_t)b * R);
+    typename D::T *w = bias + (int64_t)g * R + r;
+    *w = D::cvt(D::up(*w) - lr * acc);
+}
+
+hipError_t launch_bias_update(void *bias, const void *dz, int32_t G, int32_t B, int64_t R, float lr,
+                              int dtype, hipStream_t st)
+{
+    dim3 grid((unsigned)((R + 255) / 256), (unsigned)G);
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL(k_bias_update<BF16>, grid, dim3(256), 0, st, (uint16_t *)bias,
+                           (const uint16_t *)dz, B, R, lr);
+    else
+        hipLaunchKernelGGL(k_bias_update<F32>, grid, dim3(256), 0, st, (float *)bias,
+                           (const float *)dz, B, R, lr);
+    return hipGetLastError();
+}
+
+}  // namespace ist

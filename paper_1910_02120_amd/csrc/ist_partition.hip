@@ -1,0 +1,323 @@
+// Partition and merge kernels: neuron index tables, block gather/scatter.
+//
+// Section 2.1 "Constructing Subnets" / Appendix A of the IST paper: subnet s owns
+// the block H_l^s of each hidden layer and gets W_l[H_l^s, H_{l-1}^s].  Inside a
+// subnet the order of neurons does not change the function it computes, so the
+// packed layout keeps each block sorted by neuron id: gathers then walk the full
+// matrix in ascending address order.  ist_subnet_export undoes the sort.
+#include "ist_internal.h"
+
+namespace ist {
+
+// ----------------------------------------------------------------------------
+// index tables
+// ----------------------------------------------------------------------------
+__global__ void k_perm_invert(const int32_t *__restrict__ perm, int64_t N,
+                              int32_t *__restrict__ invpos, int32_t *err)
+{
+    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= N) return;
+    int32_t c = perm[p];
+    if (c < 0 || c >= N) { atomicOr(err, 1); return; }
+    invpos[c] = (int32_t)p;
+}
+
+__global__ void k_perm_check(const int32_t *__restrict__ perm, const int32_t *__restrict__ invpos,
+                             int64_t N, int32_t *err)
+{
+    int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= N) return;
+    int32_t p = invpos[c];
+    if (p < 0 || p >= N || perm[p] != (int32_t)c) atomicOr(err, 2);
+}
+
+// One workgroup per subnet s: walk neuron ids c in ascending order, keep those
+// whose perm position lies in block s, and number them (ordered compaction).
+constexpr int kSortThreads = 1024;
+__global__ __launch_bounds__(kSortThreads) void k_perm_sort(
+    const int32_t *__restrict__ invpos, int64_t N, int64_t w, int32_t *__restrict__ sorted,
+    int32_t *__restrict__ slot, int32_t *__restrict__ p2q)
+{
+    __shared__ int32_t wave_cnt[kSortThreads / 64];
+    __shared__ int32_t base_sh;
+    const int s = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) base_sh = 0;
+    __syncthreads();
+    for (int64_t c0 = 0; c0 < N; c0 += kSortThreads) {
+        int64_t c = c0 + threadIdx.x;
+        int32_t p = (c < N) ? invpos[c] : -1;
+        bool mine = (p >= 0) && (p < N) && (p / w == s);
+        unsigned long long bal = __ballot(mine);
+        int prefix = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wave] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+        for (int i = 0; i < kSortThreads / 64; ++i) {
+            int v = wave_cnt[i];
+            before += (i < wave) ? v : 0;
+            total += v;
+        }
+        int base = base_sh;
+        if (mine) {
+            int64_t q = (int64_t)base + before + prefix;
+            if (q < w) {   // always true for a valid permutation
+                int64_t P = (int64_t)s * w + q;
+                sorted[P] = (int32_t)c;
+                slot[c] = (int32_t)P;
+                p2q[p] = (int32_t)P;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) base_sh = base + total;
+        __syncthreads();
+    }
+}
+
+hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
+                              int32_t *sorted, int32_t *slot, int32_t *p2q, int32_t *err,
+                              hipStream_t st)
+{
+    const int th = 256;
+    const unsigned nb = (unsigned)((N + th - 1) / th);
+    hipLaunchKernelGGL(k_perm_invert, dim3(nb), dim3(th), 0, st, perm, N, invpos, err);
+    hipLaunchKernelGGL(k_perm_sort, dim3(S), dim3(kSortThreads), 0, st, invpos, N, N / S, sorted,
+                       slot, p2q);
+    return hipGetLastError();
+}
+
+hipError_t launch_perm_check(const int32_t *perm, const int32_t *invpos, int64_t N, int32_t *err,
+                             hipStream_t st)
+{
+    const int th = 256;
+    hipLaunchKernelGGL(k_perm_check, dim3((unsigned)((N + th - 1) / th)), dim3(th), 0, st, perm,
+                       invpos, N, err);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------
+// whole-row blocks (first layer: every input neuron belongs to every subnet)
+// ----------------------------------------------------------------------------
+// sub[P][:] <-> W[rows[P]][:], nc elements per row.  VEC: 16-byte moves.
+template <typename E, bool SCATTER, bool VEC>
+__global__ __launch_bounds__(256) void k_rows(E *__restrict__ W, int64_t ld, E *__restrict__ sub,
+                                              const int32_t *__restrict__ rows, int64_t nrows,
+                                              int64_t nc)
+{
+    for (int64_t P = blockIdx.x; P < nrows; P += gridDim.x) {
+        E *full = W + (int64_t)rows[P] * ld;
+        E *pack = sub + P * nc;
+        if (VEC) {
+            constexpr int per = 16 / sizeof(E);
+            const int64_t nv = nc / per;
+            uint4 *f4 = reinterpret_cast<uint4 *>(full);
+            uint4 *p4 = reinterpret_cast<uint4 *>(pack);
+            for (int64_t i = threadIdx.x; i < nv; i += blockDim.x) {
+                if (SCATTER) f4[i] = p4[i]; else p4[i] = f4[i];
+            }
+        } else {
+            for (int64_t i = threadIdx.x; i < nc; i += blockDim.x) {
+                if (SCATTER) full[i] = pack[i]; else pack[i] = full[i];
+            }
+        }
+    }
+}
+
+// Transposed first layer for sparse inputs: sub[g][c][q] <-> W[rows[g*nr+q]][c].
+// 64x64 tiles staged through LDS so both sides move along their contiguous axis.
+template <typename E, bool SCATTER>
+__global__ __launch_bounds__(256) void k_rows_transposed(E *__restrict__ W, int64_t ld,
+                                                         E *__restrict__ sub,
+                                                         const int32_t *__restrict__ rows,
+                                                         int64_t nr, int64_t nc)
+{
+    __shared__ E tile[64][65];
+    const int g = blockIdx.z;
+    const int64_t q0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 64 x 4
+    E *pack = sub + (int64_t)g * nr * nc;                     // [nc][nr]
+    if (!SCATTER) {
+        for (int i = ty; i < 64; i += 4) {
+            int64_t q = q0 + i, c = c0 + tx;
+            if (q < nr && c < nc) tile[i][tx] = W[(int64_t)rows[g * nr + q] * ld + c];
+        }
+        __syncthreads();
+        for (int i = ty; i < 64; i += 4) {
+            int64_t c = c0 + i, q = q0 + tx;
+            if (q < nr && c < nc) pack[c * nr + q] = tile[tx][i];
+        }
+    } else {
+        for (int i = ty; i < 64; i += 4) {
+            int64_t c = c0 + i, q = q0 + tx;
+            if (q < nr && c < nc) tile[tx][i] = pack[c * nr + q];
+        }
+        __syncthreads();
+        for (int i = ty; i < 64; i += 4) {
+            int64_t q = q0 + i, c = c0 + tx;
+            if (q < nr && c < nc) W[(int64_t)rows[g * nr + q] * ld + c] = tile[i][tx];
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------
+// column-partitioned blocks (middle and last layers)
+// ----------------------------------------------------------------------------
+// sub[g][i][q] <-> W[rows ? rows[g*nr+i] : i][cols[g*nc+q]]
+template <typename E, bool SCATTER>
+__global__ __launch_bounds__(256) void k_cols(E *__restrict__ W, int64_t ld, E *__restrict__ sub,
+                                              const int32_t *__restrict__ rows,
+                                              const int32_t *__restrict__ cols, int64_t nr,
+                                              int64_t nc)
+{
+    const int g = blockIdx.z;
+    const int64_t i = blockIdx.y;
+    const int64_t r = rows ? (int64_t)rows[g * nr + i] : i;
+    E *full = W + r * ld;
+    E *pack = sub + ((int64_t)g * nr + i) * nc;
+    const int32_t *cg = cols + (int64_t)g * nc;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nc;
+         q += (int64_t)gridDim.x * blockDim.x) {
+        if (SCATTER) full[cg[q]] = pack[q]; else pack[q] = full[cg[q]];
+    }
+}
+
+template <typename E, bool SCATTER>
+static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
+{
+    E *W = static_cast<E *>(a.W);
+    E *sub = static_cast<E *>(a.sub);
+    if (a.transposed) {
+        dim3 grid((unsigned)((a.nc + 63) / 64), (unsigned)((a.nr + 63) / 64), (unsigned)a.G);
+        hipLaunchKernelGGL((k_rows_transposed<E, SCATTER>), grid, dim3(256), 0, st, W, a.ld, sub,
+                           a.rows, a.nr, a.nc);
+    } else if (a.cols == nullptr) {
+        const int64_t nrows = a.nr * a.G;
+        const bool vec = ((a.nc * sizeof(E)) % 16 == 0) && ((a.ld * sizeof(E)) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(W) % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(sub) % 16 == 0);
+        unsigned nb = (unsigned)(nrows < 65536 ? nrows : 65536);
+        if (vec)
+            hipLaunchKernelGGL((k_rows<E, SCATTER, true>), dim3(nb), dim3(256), 0, st, W, a.ld, sub,
+                               a.rows, nrows, a.nc);
+        else
+            hipLaunchKernelGGL((k_rows<E, SCATTER, false>), dim3(nb), dim3(256), 0, st, W, a.ld,
+                               sub, a.rows, nrows, a.nc);
+    } else {
+        unsigned gx = (unsigned)((a.nc + 255) / 256);
+        if (gx > 64) gx = 64;
+        // grid.y is limited to 65535 blocks: split very tall blocks into several launches
+        const int64_t max_y = 65535;
+        for (int64_t i0 = 0; i0 < a.nr; i0 += max_y) {
+            int64_t ny = a.nr - i0 < max_y ? a.nr - i0 : max_y;
+            // rows == nullptr means identity rows: shift the matrix and block pointers instead
+            if (a.rows) {
+                // per-group row lists are indexed by g*nr + i: cannot shift, so the kernel
+                // takes nr as the stride and we require nr <= max_y for this case
+                if (a.nr > max_y) return hipErrorInvalidValue;
+                hipLaunchKernelGGL((k_cols<E, SCATTER>), dim3(gx, (unsigned)ny, (unsigned)a.G),
+                                   dim3(256), 0, st, W, a.ld, sub, a.rows, a.cols, a.nr, a.nc);
+            } else {
+                for (int32_t g = 0; g < a.G; ++g)
+                    hipLaunchKernelGGL((k_cols<E, SCATTER>), dim3(gx, (unsigned)ny, 1), dim3(256), 0,
+                                       st, W + i0 * a.ld, a.ld,
+                                       sub + ((int64_t)g * a.nr + i0) * a.nc,
+                                       (const int32_t *)nullptr, a.cols + (int64_t)g * a.nc, a.nr,
+                                       a.nc);
+            }
+        }
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_partition_copy(const CopyArgs &a, hipStream_t st)
+{
+    return a.esz == 2 ? copy_typed<uint16_t, false>(a, st) : copy_typed<uint32_t, false>(a, st);
+}
+hipError_t launch_merge_copy(const CopyArgs &a, hipStream_t st)
+{
+    return a.esz == 2 ? copy_typed<uint16_t, true>(a, st) : copy_typed<uint32_t, true>(a, st);
+}
+
+// ----------------------------------------------------------------------------
+// output bias: replicate on partition, mean on merge
+// ----------------------------------------------------------------------------
+template <typename E>
+__global__ void k_bias_replicate(const E *__restrict__ b, E *__restrict__ sub, int64_t n, int32_t G)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    E v = b[i];
+    for (int g = 0; g < G; ++g) sub[(int64_t)g * n + i] = v;
+}
+
+template <typename D>
+__global__ void k_bias_mean(typename D::T *__restrict__ b, const typename D::T *__restrict__ sub,
+                            int64_t n, int32_t G)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float acc = 0.0f;
+    for (int g = 0; g < G; ++g) acc += D::ld(sub + (int64_t)g * n + i);
+    b[i] = D::cvt(acc * (1.0f / (float)G));
+}
+
+hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G, int esz,
+                                 hipStream_t st)
+{
+    dim3 grid((unsigned)((n + 255) / 256));
+    if (esz == 2)
+        hipLaunchKernelGGL(k_bias_replicate<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)b,
+                           (uint16_t *)sub, n, G);
+    else
+        hipLaunchKernelGGL(k_bias_replicate<uint32_t>, grid, dim3(256), 0, st, (const uint32_t *)b,
+                           (uint32_t *)sub, n, G);
+    return hipGetLastError();
+}
+
+hipError_t launch_bias_mean(void *b, const void *sub, int64_t n, int32_t G, int dtype,
+                            hipStream_t st)
+{
+    dim3 grid((unsigned)((n + 255) / 256));
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL(k_bias_mean<BF16>, grid, dim3(256), 0, st, (uint16_t *)b,
+                           (const uint16_t *)sub, n, G);
+    else
+        hipLaunchKernelGGL(k_bias_mean<F32>, grid, dim3(256), 0, st, (float *)b, (const float *)sub,
+                           n, G);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------
+// export one subnet block in permutation order
+// ----------------------------------------------------------------------------
+template <typename E>
+__global__ void k_export(const E *__restrict__ sub, E *__restrict__ dst, int64_t nr, int64_t nc,
+                         const int32_t *__restrict__ p2q_r, int64_t base_r,
+                         const int32_t *__restrict__ p2q_c, int64_t base_c, bool transposed)
+{
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nr * nc) return;
+    int64_t i = idx / nc, j = idx % nc;
+    int64_t qi = p2q_r ? (int64_t)p2q_r[base_r + i] - base_r : i;
+    int64_t qj = p2q_c ? (int64_t)p2q_c[base_c + j] - base_c : j;
+    if (qi < 0 || qi >= nr || qj < 0 || qj >= nc) return;
+    dst[idx] = transposed ? sub[qj * nr + qi] : sub[qi * nc + qj];
+}
+
+hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc, const int32_t *p2q_r,
+                         int64_t base_r, const int32_t *p2q_c, int64_t base_c, bool transposed,
+                         int esz, hipStream_t st)
+{
+    int64_t n = nr * nc;
+    if (n == 0) return hipSuccess;
+    dim3 grid((unsigned)((n + 255) / 256));
+    if (esz == 2)
+        hipLaunchKernelGGL(k_export<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)sub,
+                           (uint16_t *)dst, nr, nc, p2q_r, base_r, p2q_c, base_c, transposed);
+    else
+        hipLaunchKernelGGL(k_export<uint32_t>, grid, dim3(256), 0, st, (const uint32_t *)sub,
+                           (uint32_t *)dst, nr, nc, p2q_r, base_r, p2q_c, base_c, transposed);
+    return hipGetLastError();
+}
+
+}  // namespace ist

@@ -1,0 +1,188 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Partition / merge indexing must be bit-exact.  Parameters after k local steps
+must agree within max relative error 2e-3 (f32) or 3e-2 (bf16), measured per
+parameter tensor as ||gpu - oracle||_inf / ||oracle||_inf.
+"""
+import numpy as np
+import pytest
+import torch
+
+import ist_inputs as gen
+from oracle import ist_oracle as orc
+
+import ist_harness as H
+
+pytestmark = pytest.mark.gpu
+
+C = gen.CONFIGS
+
+
+def _mk(name, base, **kw):
+    return gen.scaled(C[base], name=name, **kw)
+
+
+# reduced shapes: several tiles plus ragged tails in every dimension
+SHAPES = {
+    "cfg1": C["cfg1"],
+    "cfg1-nobias-S1": _mk("cfg1-S1", "cfg1", S=1),
+    "ragged-f32": _mk("ragged-f32", "cfg2", dims=(100, 156, 204, 35), S=4, B=37, k=3, lr=0.05),
+    "ragged-bf16": _mk("ragged-bf16", "cfg3", dims=(150, 264, 136, 10), S=8, B=45, k=4, lr=0.05),
+    "cfg3-small": _mk("cfg3-small", "cfg3", dims=(384, 1024, 1024, 10), k=5, lr=0.05),
+    "cfg4-small": _mk("cfg4-small", "cfg4", dims=(256, 1024, 512, 1024, 100), B=96, k=3, lr=0.05),
+    "cfg5-small": _mk("cfg5-small", "cfg5", dims=(3001, 256, 5003), S=8, B=40, k=3, nnz_per_row=20,
+                      lr=0.5),
+    "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
+                   dtype="f32", lr=0.5),
+}
+
+
+def _dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return "cuda:0"
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_partition_and_merge_are_bit_exact(name):
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, has_bias="nobias" not in name, dev=_dev())
+    ctx = P.context()
+    ctx.set_checked(True)
+    ctx.partition(P.dW, P.db, P.dperm)
+    got = H.export_all(ctx, cfg)
+    raw_W = [H.np_bits(w, cfg.dtype) for w in P.Ws]
+    raw_b = [H.np_bits(b, cfg.dtype) for b in P.bs] if P.has_bias else [None] * cfg.t
+    want = orc.partition(raw_W, raw_b, P.perms, cfg.S)
+    for s in range(cfg.S):
+        for l in range(cfg.t):
+            assert np.array_equal(H.bits(got[s][0][l]), want[s][0][l]), (name, s, l)
+            if P.has_bias:
+                assert np.array_equal(H.bits(got[s][1][l]), want[s][1][l]), (name, s, l, "bias")
+    # merge(partition(W)) == W, into buffers that were poisoned first: what no subnet
+    # owns must keep the poison, everything else must return bit for bit
+    poison = [torch.full_like(w, 7.0) for w in P.dW]
+    pb = [torch.full_like(b, 7.0) for b in P.db] if P.has_bias else None
+    ctx.merge(poison, pb)
+    torch.cuda.synchronize()
+    full = [np.full(w.shape, H.np_bits(np.float32([7.0]), cfg.dtype)[0], dtype=raw_W[0].dtype)
+            for w in raw_W]
+    orc.merge(full, None, P.perms, cfg.S, want)
+    for l in range(cfg.t):
+        assert np.array_equal(H.bits(poison[l]), full[l]), (name, l)
+    if P.has_bias:
+        for l in range(cfg.t):
+            assert np.array_equal(H.bits(pb[l]), raw_b[l]), (name, l, "bias round trip")
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_k_local_steps_match_oracle(name):
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, has_bias="nobias" not in name, dev=_dev())
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    loss = P.gpu_steps(ctx)
+    got = H.export_all(ctx, cfg)
+    subs = P.oracle_subnets()
+    want_loss = P.oracle_steps(subs)
+    tol = H.TOL[cfg.dtype]
+    worst = H.compare_subnets(got, subs, cfg, tol)
+    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
+    # and the merged full network: owned entries from the subnets, the rest untouched
+    Wm = [w.clone() for w in P.dW]
+    bm = [b.clone() for b in P.db] if P.has_bias else None
+    ctx.merge(Wm, bm)
+    torch.cuda.synchronize()
+    typed = [([H.np_bits(H.to_f32(w), cfg.dtype) for w in Wl],
+              [None if b is None else H.to_f32(b) for b in bl]) for Wl, bl in got]
+    full = [H.np_bits(w, cfg.dtype).copy() for w in P.Ws]
+    orc.merge(full, None, P.perms, cfg.S, typed)
+    for l in range(cfg.t):
+        assert np.array_equal(H.bits(Wm[l]), full[l]), (name, l, "merge of trained subnets")
+    if P.has_bias:
+        fb = [b.astype(np.float32).copy() for b in P.bs]
+        fl = [w.astype(np.float32).copy() for w in P.Ws]
+        f32subs = [([H.to_f32(w) for w in Wl], [H.to_f32(b) for b in bl]) for Wl, bl in got]
+        orc.merge(fl, fb, P.perms, cfg.S, f32subs, mode=cfg.dtype)
+        for l in range(cfg.t):
+            np.testing.assert_array_equal(H.to_f32(bm[l]), fb[l])
+    print(f"{name}: worst parameter rel err {worst:.3e} (tol {tol})")
+    ctx.close()
+
+
+def test_steps_can_be_split_and_batches_reused():
+    """Two calls of k/2 steps equal one call of k steps; stride 0 reuses a batch."""
+    cfg = SHAPES["ragged-f32"]
+    P = H.Problem(cfg, dev=_dev())
+    a, b = P.context(), P.context()
+    a.partition(P.dW, P.db, P.dperm)
+    b.partition(P.dW, P.db, P.dperm)
+    a.subnet_steps(P.dy, cfg.lr, 2, cfg.B, X=P.dX, stride_s=cfg.k * cfg.B, stride_k=cfg.B)
+    b.subnet_steps(P.dy, cfg.lr, 1, cfg.B, X=P.dX, stride_s=cfg.k * cfg.B, stride_k=cfg.B)
+    off = cfg.B
+    b.subnet_steps(P.dy[off:], cfg.lr, 1, cfg.B, X=P.dX.reshape(-1, cfg.dims[0])[off:],
+                   stride_s=cfg.k * cfg.B, stride_k=cfg.B)
+    ga, gb = H.export_all(a, cfg), H.export_all(b, cfg)
+    for s in range(cfg.S):
+        for l in range(cfg.t):
+            assert torch.equal(ga[s][0][l], gb[s][0][l])
+    # same batch for every subnet and step: oracle fed with the repeated batch
+    c = P.context()
+    c.partition(P.dW, P.db, P.dperm)
+    c.subnet_steps(P.dy, cfg.lr, 2, cfg.B, X=P.dX, stride_s=0, stride_k=0)
+    subs = P.oracle_subnets()
+    Xr = np.broadcast_to(P.X[0, 0], (cfg.S, 2) + P.X.shape[2:]).copy()
+    yr = np.broadcast_to(P.y[0, 0], (cfg.S, 2, cfg.B)).copy()
+    orc.subnet_steps(subs, cfg.lr, 2, "f32", yr, X=Xr)
+    H.compare_subnets(H.export_all(c, cfg), subs, cfg, H.TOL["f32"])
+    for x in (a, b, c):
+        x.close()
+
+
+def test_error_paths():
+    from paper_1910_02120_amd import ISTContext, ISTError
+    cfg = SHAPES["ragged-f32"]
+    P = H.Problem(cfg, dev=_dev())
+    ctx = P.context()
+    with pytest.raises(ISTError) as e:
+        ctx.subnet_steps(P.dy, cfg.lr, 1, cfg.B, X=P.dX)
+    assert e.value.status == -6                       # steps before partition
+    with pytest.raises(ISTError) as e:
+        ctx.merge(P.dW, P.db)
+    assert e.value.status == -6
+    ctx.set_checked(True)
+    bad = [p.clone() for p in P.dperm]
+    bad[0][3] = bad[0][4]                             # duplicate -> not a permutation
+    with pytest.raises(ISTError) as e:
+        ctx.partition(P.dW, P.db, bad)
+    assert e.value.status == -3
+    bad[0][3] = 10 ** 6                               # out of range
+    with pytest.raises(ISTError) as e:
+        ctx.partition(P.dW, P.db, bad)
+    assert e.value.status == -3
+    # unchecked mode with the same bad permutation must stay in bounds (no fault)
+    ctx.set_checked(False)
+    ctx.partition(P.dW, P.db, bad)
+    torch.cuda.synchronize()
+    ctx.partition(P.dW, P.db, P.dperm)
+    with pytest.raises(ISTError) as e:
+        ctx.subnet_steps(P.dy, cfg.lr, 1, cfg.B + 1, X=P.dX)
+    assert e.value.status == -2                       # B > max_B
+    with pytest.raises(ISTError) as e:
+        ISTContext((8, 10, 4), 4, bind=False)
+    assert e.value.status == -2
+    ctx.close()
+
+
+def test_k_zero_and_empty_step_list():
+    cfg = SHAPES["cfg1"]
+    P = H.Problem(cfg, dev=_dev())
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    before = H.export_all(ctx, cfg)
+    ctx.subnet_steps(P.dy, cfg.lr, 0, cfg.B, X=P.dX)
+    after = H.export_all(ctx, cfg)
+    for s in range(cfg.S):
+        for l in range(cfg.t):
+            assert torch.equal(before[s][0][l], after[s][0][l])
+    ctx.close()
