@@ -144,6 +144,20 @@ ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, voi
 /* Rows and columns of subnet layer l as ist_subnet_export writes them. */
 ist_status ist_subnet_shape(const ist_ctx *ctx, int32_t l, int64_t *rows, int64_t *cols);
 
+/*
+ * Measurement support.  With profiling on, every kernel launch of the three hot
+ * calls is bracketed by HIP events on the caller's stream (this perturbs timing
+ * slightly; leave it off for throughput runs).  ist_profile_read synchronises
+ * with the last recorded event and returns, for one kernel class, the summed
+ * kernel time in milliseconds and the number of launches since the last reset.
+ * Kernel classes are numbered 0 .. ist_profile_classes()-1.
+ */
+ist_status ist_profile_enable(ist_ctx *ctx, int32_t on);
+ist_status ist_profile_reset(ist_ctx *ctx);
+ist_status ist_profile_read(ist_ctx *ctx, int32_t kernel_class, double *total_ms, int64_t *launches);
+int32_t ist_profile_classes(void);
+const char *ist_profile_class_name(int32_t kernel_class);
+
 const char *ist_last_error(const ist_ctx *ctx);
 const char *ist_version(void);
 

@@ -23,7 +23,8 @@ IST_DENSE, IST_CSR = 0, 1
 
 EXPORTS = ["ist_create", "ist_destroy", "ist_subnets_bytes", "ist_workspace_bytes", "ist_bind",
            "ist_set_checked", "ist_partition", "ist_subnet_steps", "ist_merge", "ist_subnet_export",
-           "ist_subnet_shape", "ist_last_error", "ist_version"]
+           "ist_subnet_shape", "ist_last_error", "ist_version", "ist_profile_enable",
+           "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name"]
 
 
 class ISTError(RuntimeError):
@@ -71,8 +72,14 @@ def load_library() -> C.CDLL:
     lib.ist_merge.argtypes = [p, C.POINTER(_Params), p]
     lib.ist_subnet_export.argtypes = [p, C.c_int32, C.c_int32, p, p, p]
     lib.ist_subnet_shape.argtypes = [p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.ist_profile_enable.argtypes = [p, C.c_int32]
+    lib.ist_profile_reset.argtypes = [p]
+    lib.ist_profile_read.argtypes = [p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.ist_profile_classes.argtypes = []
+    lib.ist_profile_class_name.argtypes = [C.c_int32]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int32
+    lib.ist_profile_class_name.restype = C.c_char_p
     lib.ist_last_error.argtypes = [p]
     lib.ist_last_error.restype = C.c_char_p
     lib.ist_version.argtypes = []
@@ -217,6 +224,23 @@ class ISTContext:
                                                b.data_ptr() if b is not None else None,
                                                _stream_ptr(stream)))
         return W, b
+
+    # -- measurement ------------------------------------------------------
+    def profile_enable(self, on: bool):
+        self._check(self.lib.ist_profile_enable(self._ctx, 1 if on else 0))
+
+    def profile_reset(self):
+        self._check(self.lib.ist_profile_reset(self._ctx))
+
+    def profile_read(self):
+        """{kernel class: (total_ms, launches)} since the last reset (synchronises)."""
+        out = {}
+        for c in range(self.lib.ist_profile_classes()):
+            ms, n = C.c_double(), C.c_int64()
+            self._check(self.lib.ist_profile_read(self._ctx, c, C.byref(ms), C.byref(n)))
+            if n.value:
+                out[self.lib.ist_profile_class_name(c).decode()] = (ms.value, n.value)
+        return out
 
     def close(self):
         if getattr(self, "_ctx", None) and self._ctx.value:

@@ -32,6 +32,46 @@ ist_status hip_fail(ist_ctx *ctx, hipError_t e, const char *where)
         if (e_ != hipSuccess) return hip_fail(ctx, e_, where); \
     } while (0)
 
+const char *kClassNames[KC_COUNT] = {
+    "perm_tables", "partition_copy", "merge_copy", "bias_copy", "gemm_forward", "gemm_backward_data",
+    "gemm_update", "softmax_xent", "loss_reduce", "bias_update", "csr_forward", "csr_update"};
+
+hipEvent_t prof_event(ist_ctx *ctx)
+{
+    if (!ctx->prof_free.empty()) {
+        hipEvent_t e = ctx->prof_free.back();
+        ctx->prof_free.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void prof_begin(ist_ctx *ctx, int cls, hipStream_t st)
+{
+    if (!ctx->prof_on) return;
+    ist_ctx::ProfRec r{cls, prof_event(ctx), prof_event(ctx)};
+    if (!r.start || !r.stop) return;
+    (void)hipEventRecord(r.start, st);
+    ctx->prof_recs.push_back(r);
+}
+
+void prof_end(ist_ctx *ctx, hipStream_t st)
+{
+    if (!ctx->prof_on || ctx->prof_recs.empty()) return;
+    (void)hipEventRecord(ctx->prof_recs.back().stop, st);
+}
+
+// launch one kernel class, bracketed by events when profiling is on
+#define IST_RUN(cls, call, where)                              \
+    do {                                                       \
+        prof_begin(ctx, cls, st);                              \
+        hipError_t e_ = (call);                                \
+        prof_end(ctx, st);                                     \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, where); \
+    } while (0)
+
 inline const int32_t *tbl(const ist_ctx *ctx, size_t off)
 {
     return reinterpret_cast<const int32_t *>(ctx->subnets + off);
@@ -135,7 +175,49 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
 
 ist_status ist_destroy(ist_ctx *ctx)
 {
+    if (ctx) {
+        for (auto &r : ctx->prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+        for (auto e : ctx->prof_free) (void)hipEventDestroy(e);
+    }
     delete ctx;
+    return IST_OK;
+}
+
+int32_t ist_profile_classes(void) { return KC_COUNT; }
+
+const char *ist_profile_class_name(int32_t c) { return (c >= 0 && c < KC_COUNT) ? kClassNames[c] : ""; }
+
+ist_status ist_profile_enable(ist_ctx *ctx, int32_t on)
+{
+    if (!ctx) return IST_EINVAL;
+    ctx->prof_on = on != 0;
+    return IST_OK;
+}
+
+ist_status ist_profile_reset(ist_ctx *ctx)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->prof_recs.empty()) IST_HIP(hipEventSynchronize(ctx->prof_recs.back().stop), "profile reset");
+    for (auto &r : ctx->prof_recs) { ctx->prof_free.push_back(r.start); ctx->prof_free.push_back(r.stop); }
+    ctx->prof_recs.clear();
+    return IST_OK;
+}
+
+ist_status ist_profile_read(ist_ctx *ctx, int32_t cls, double *total_ms, int64_t *launches)
+{
+    if (!ctx || !total_ms || !launches || cls < 0 || cls >= KC_COUNT) return IST_EINVAL;
+    double tot = 0.0;
+    int64_t n = 0;
+    if (!ctx->prof_recs.empty()) IST_HIP(hipEventSynchronize(ctx->prof_recs.back().stop), "profile read");
+    for (auto &r : ctx->prof_recs) {
+        if (r.cls != cls) continue;
+        float ms = 0.0f;
+        IST_HIP(hipEventElapsedTime(&ms, r.start, r.stop), "profile read");
+        tot += ms;
+        ++n;
+    }
+    *total_ms = tot;
+    *launches = n;
     return IST_OK;
 }
 
@@ -225,13 +307,13 @@ ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *
     for (int l = 1; l < t; ++l) {
         const HiddenPlan &h = ctx->hidden[l - 1];
         int32_t *invpos = reinterpret_cast<int32_t *>(ctx->workspace + h.off_invpos);
-        IST_HIP(launch_perm_tables(perm[l - 1], h.N, S, invpos,
+        IST_RUN(KC_PERM_TABLES, launch_perm_tables(perm[l - 1], h.N, S, invpos,
                                    reinterpret_cast<int32_t *>(ctx->subnets + h.off_sorted),
                                    reinterpret_cast<int32_t *>(ctx->subnets + h.off_slot),
                                    reinterpret_cast<int32_t *>(ctx->subnets + h.off_p2q),
                                    ctx->errflag(), st), "perm tables");
         if (ctx->checked)
-            IST_HIP(launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");
+            IST_RUN(KC_PERM_TABLES, launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");
     }
     if (ctx->checked) {
         int32_t flag = 0;
@@ -243,16 +325,16 @@ ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
         CopyArgs a = copy_args(ctx, l, params->W[l - 1]);
-        IST_HIP(launch_partition_copy(a, st), "partition copy");
+        IST_RUN(KC_PARTITION_COPY, launch_partition_copy(a, st), "partition copy");
         if (ctx->has_bias) {
             if (l < t) {
                 CopyArgs b{};
                 b.W = params->b[l - 1]; b.ld = 1; b.sub = ctx->subnets + L.off_b;
                 b.rows = a.rows; b.cols = nullptr; b.nr = L.R; b.nc = 1; b.G = S; b.esz = e;
                 b.N_out = L.N_out; b.N_in = 1; b.transposed = false;
-                IST_HIP(launch_partition_copy(b, st), "partition bias");
+                IST_RUN(KC_BIAS_COPY, launch_partition_copy(b, st), "partition bias");
             } else {
-                IST_HIP(launch_bias_replicate(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, e, st),
+                IST_RUN(KC_BIAS_COPY, launch_bias_replicate(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, e, st),
                         "replicate output bias");
             }
         }
@@ -272,16 +354,16 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream)
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
         CopyArgs a = copy_args(ctx, l, params->W[l - 1]);
-        IST_HIP(launch_merge_copy(a, st), "merge copy");
+        IST_RUN(KC_MERGE_COPY, launch_merge_copy(a, st), "merge copy");
         if (ctx->has_bias) {
             if (l < t) {
                 CopyArgs b{};
                 b.W = params->b[l - 1]; b.ld = 1; b.sub = ctx->subnets + L.off_b;
                 b.rows = a.rows; b.cols = nullptr; b.nr = L.R; b.nc = 1; b.G = S; b.esz = e;
                 b.N_out = L.N_out; b.N_in = 1; b.transposed = false;
-                IST_HIP(launch_merge_copy(b, st), "merge bias");
+                IST_RUN(KC_BIAS_COPY, launch_merge_copy(b, st), "merge bias");
             } else {
-                IST_HIP(launch_bias_mean(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, ctx->dtype, st),
+                IST_RUN(KC_BIAS_COPY, launch_bias_mean(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, ctx->dtype, st),
                         "mean output bias");
             }
         }
@@ -340,7 +422,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             const void *bias = ctx->has_bias ? sb + L.off_b : nullptr;
             if (l == 1 && csr) {
                 CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R};
-                IST_HIP(launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act, dt, st), "csr forward");
+                IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act, dt, st), "csr forward");
                 continue;
             }
             GemmArgs a{};
@@ -356,15 +438,15 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             a.C = ws + L.off_act; a.ldc = L.R; a.gC = (int64_t)B * L.R;
             a.M = B; a.N = (int32_t)L.R; a.K = (int32_t)L.C; a.G = S;
             a.bias = bias; a.gBias = L.R;
-            IST_HIP(launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
+            IST_RUN(KC_GEMM_FWD, launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
         }
         // ---------------- loss and dz_t ----------------
         {
             const LayerPlan &L = ctx->layer[t - 1];
-            IST_HIP(launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
+            IST_RUN(KC_SOFTMAX_XENT, launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
                                         bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, dt, st),
                     "softmax cross-entropy");
-            if (loss_out) IST_HIP(launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
+            if (loss_out) IST_RUN(KC_LOSS_REDUCE, launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
         }
         // ---------------- backward + update, top layer first ----------------
         for (int l = t; l >= 1; --l) {
@@ -377,11 +459,11 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.C = ws + P.off_dz; a.ldc = L.C; a.gC = (int64_t)B * L.C;
                 a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
                 a.mask = ws + P.off_act; a.ldm = L.C; a.gMask = (int64_t)B * L.C;
-                IST_HIP(launch_gemm(dt, EPI_BWD_DATA, a, st), "backward-data gemm");
+                IST_RUN(KC_GEMM_BWD_DATA, launch_gemm(dt, EPI_BWD_DATA, a, st), "backward-data gemm");
             }
             if (l == 1 && csr) {
                 CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R};
-                IST_HIP(launch_csr_update(c, sb + L.off_W, ws + L.off_dz,
+                IST_RUN(KC_CSR_UPDATE, launch_csr_update(c, sb + L.off_W, ws + L.off_dz,
                                           reinterpret_cast<uint32_t *>(ws + ctx->off_bitmap), lr, dt, st),
                         "csr update");
             } else {       // W_l <- W_l - lr * dz_l^T h_{l-1}
@@ -398,10 +480,10 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.C = sb + L.off_W; a.ldc = L.C; a.gC = L.R * L.C;
                 a.M = (int32_t)L.R; a.N = (int32_t)L.C; a.K = B; a.G = S;
                 a.lr = lr;
-                IST_HIP(launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
+                IST_RUN(KC_GEMM_UPDATE, launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
             }
             if (ctx->has_bias)
-                IST_HIP(launch_bias_update(sb + L.off_b, ws + L.off_dz, S, B, L.R, lr, dt, st), "bias update");
+                IST_RUN(KC_BIAS_UPDATE, launch_bias_update(sb + L.off_b, ws + L.off_dz, S, B, L.R, lr, dt, st), "bias update");
         }
     }
     return IST_OK;

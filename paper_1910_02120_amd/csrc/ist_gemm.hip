@@ -8,6 +8,9 @@
 //
 // This file holds the generic kernel: any strides, any alignment, fp32 FMA with
 // LDS tiles.  It is the fallback for shapes the MFMA kernels do not take.
+#include <cstdlib>
+#include <string>
+
 #include "ist_internal.h"
 
 namespace ist {
@@ -105,11 +108,21 @@ static hipError_t launch_typed(int epi, const GemmArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
+hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0 || a.G <= 0) return hipSuccess;
     if ((a.M + GBM - 1) / GBM > 65535) return hipErrorInvalidValue;
     return dtype == IST_BF16 ? launch_typed<BF16>(epi, a, st) : launch_typed<F32>(epi, a, st);
+}
+
+// IST_GEMM=generic in the environment selects the plain FMA kernel (debugging aid).
+hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
+{
+    static const bool force_generic = [] {
+        const char *e = getenv("IST_GEMM");
+        return e && std::string(e) == "generic";
+    }();
+    return force_generic ? launch_gemm_generic(dtype, epi, a, st) : launch_gemm_mfma(dtype, epi, a, st);
 }
 
 }  // namespace ist

@@ -75,11 +75,23 @@ struct ist_ctx {
     int32_t checked = 0;
     std::string err;
 
+    // optional per-kernel-class timing (HIP events around every launch)
+    struct ProfRec { int cls; hipEvent_t start, stop; };
+    bool prof_on = false;
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> prof_free;
+
     int esz() const { return dtype == IST_BF16 ? 2 : 4; }
     int32_t *errflag() const { return reinterpret_cast<int32_t *>(workspace + off_err); }
 };
 
 namespace ist {
+
+enum KernelClass {
+    KC_PERM_TABLES = 0, KC_PARTITION_COPY, KC_MERGE_COPY, KC_BIAS_COPY, KC_GEMM_FWD, KC_GEMM_BWD_DATA,
+    KC_GEMM_UPDATE, KC_SOFTMAX_XENT, KC_LOSS_REDUCE, KC_BIAS_UPDATE, KC_CSR_FORWARD, KC_CSR_UPDATE,
+    KC_COUNT
+};
 
 // ----------------------------------------------------------------- partition / merge
 hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
@@ -125,6 +137,8 @@ struct GemmArgs {
     float lr;                                 // EPI_UPDATE: C = C - lr * acc
 };
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
