@@ -482,8 +482,18 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.lr = lr;
                 IST_RUN(KC_GEMM_UPDATE, launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
             }
-            if (ctx->has_bias)
-                IST_RUN(KC_BIAS_UPDATE, launch_bias_update(sb + L.off_b, ws + L.off_dz, S, B, L.R, lr, dt, st), "bias update");
+        }
+        // all bias updates of the step in one launch (they only need the dz_l of this step)
+        if (ctx->has_bias) {
+            for (int l0 = 1; l0 <= t; l0 += kMaxBiasJobs) {
+                BiasArgs ba{};
+                ba.B = B; ba.G = S; ba.lr = lr;
+                for (int l = l0; l <= t && l < l0 + kMaxBiasJobs; ++l) {
+                    const LayerPlan &L = ctx->layer[l - 1];
+                    ba.job[ba.njobs++] = BiasJob{sb + L.off_b, ws + L.off_dz, L.R, 0};
+                }
+                IST_RUN(KC_BIAS_UPDATE, launch_bias_update(ba, dt, st), "bias update");
+            }
         }
     }
     return IST_OK;

@@ -145,8 +145,10 @@ hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_
                                int dtype, hipStream_t st);
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
                               int32_t G, int32_t B, hipStream_t st);
-hipError_t launch_bias_update(void *bias, const void *dz, int32_t G, int32_t B, int64_t R,
-                              float lr, int dtype, hipStream_t st);
+struct BiasJob { void *bias; const void *dz; int64_t R; int32_t blk0; };
+constexpr int kMaxBiasJobs = 16;
+struct BiasArgs { BiasJob job[kMaxBiasJobs]; int32_t njobs, B, G; float lr; };
+hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st);
 
 // sparse-input first layer (weights stored [G][N0][w])
 struct CsrArgs {

@@ -107,32 +107,46 @@ hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out
     return hipGetLastError();
 }
 
-// b[g][r] <- b[g][r] - lr * sum_b dz[g][b][r]
+// b_l[g][r] <- b_l[g][r] - lr * sum_b dz_l[g][b][r] for several layers in one launch.
+// A workgroup owns 64 columns of one (layer, subnet); its 4 wavefronts split the
+// batch rows, partial sums meet in LDS, summation order is fixed.
 template <typename D>
-__global__ __launch_bounds__(256) void k_bias_update(typename D::T *__restrict__ bias,
-                                                     const typename D::T *__restrict__ dz,
-                                                     int32_t B, int64_t R, float lr)
+__global__ __launch_bounds__(256) void k_bias_update(BiasArgs a)
 {
-    const int g = blockIdx.y;
-    int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= R) return;
-    const typename D::T *p = dz + (int64_t)g * B * R + r;
+    using T = typename D::T;
+    __shared__ float part[4][64];
+    int j = 0;
+    while (j + 1 < a.njobs && (int)blockIdx.x >= a.job[j + 1].blk0) ++j;
+    const BiasJob jb = a.job[j];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)(blockIdx.x - jb.blk0) * 64 + lane;
     float acc = 0.0f;
-    for (int b = 0; b < B; ++b) acc += D::ld(p + (int64_t)b * R);
-    typename D::T *w = bias + (int64_t)g * R + r;
-    *w = D::cvt(D::up(*w) - lr * acc);
+    if (r < jb.R) {
+        const T *p = static_cast<const T *>(jb.dz) + (int64_t)g * a.B * jb.R + r;
+        for (int b = wave; b < a.B; b += 4) acc += D::ld(p + (int64_t)b * jb.R);
+    }
+    part[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && r < jb.R) {
+        float tot = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+        T *w = static_cast<T *>(jb.bias) + (int64_t)g * jb.R + r;
+        *w = D::cvt(D::up(*w) - a.lr * tot);
+    }
 }
 
-hipError_t launch_bias_update(void *bias, const void *dz, int32_t G, int32_t B, int64_t R, float lr,
-                              int dtype, hipStream_t st)
+hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st)
 {
-    dim3 grid((unsigned)((R + 255) / 256), (unsigned)G);
+    if (a.njobs <= 0) return hipSuccess;
+    int blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        a.job[j].blk0 = blocks;
+        blocks += (int)((a.job[j].R + 63) / 64);
+    }
+    dim3 grid((unsigned)blocks, (unsigned)a.G);
     if (dtype == IST_BF16)
-        hipLaunchKernelGGL(k_bias_update<BF16>, grid, dim3(256), 0, st, (uint16_t *)bias,
-                           (const uint16_t *)dz, B, R, lr);
+        hipLaunchKernelGGL(k_bias_update<BF16>, grid, dim3(256), 0, st, a);
     else
-        hipLaunchKernelGGL(k_bias_update<F32>, grid, dim3(256), 0, st, (float *)bias,
-                           (const float *)dz, B, R, lr);
+        hipLaunchKernelGGL(k_bias_update<F32>, grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
