@@ -1,6 +1,8 @@
 // C ABI of the IST library: host-side plan, argument checks and kernel sequencing.
 // See include/ist.h for the contract of every entry point.
+#include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -71,6 +73,13 @@ void prof_end(ist_ctx *ctx, hipStream_t st)
         prof_end(ctx, st);                                     \
         if (e_ != hipSuccess) return hip_fail(ctx, e_, where); \
     } while (0)
+
+inline void set_split(const ist_ctx *ctx, GemmArgs &a)
+{
+    a.partial = ctx->partial_bytes ? reinterpret_cast<float *>(ctx->workspace + ctx->off_partial) : nullptr;
+    a.partial_bytes = ctx->partial_bytes;
+    a.zeros = ctx->workspace + ctx->off_zeros;
+}
 
 inline const int32_t *tbl(const ist_ctx *ctx, size_t off)
 {
@@ -145,6 +154,7 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         L.R = L.row_part ? L.N_out / S : L.N_out;
         L.C = L.col_part ? L.N_in / S : L.N_in;
         L.transposed = (l == 1 && d->input == IST_CSR);
+        L.ldr = (L.R + 7) / 8 * 8;
         L.off_W = off; off = align_up(off + (size_t)S * L.R * L.C * e);
         L.off_b = off; off = align_up(off + (size_t)S * L.R * e);
     }
@@ -160,14 +170,28 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     for (int l = 1; l <= t; ++l) {
         LayerPlan &L = ctx->layer[l - 1];
         size_t act_e = (l == t) ? sizeof(float) : (size_t)e;
-        L.off_act = w; w = align_up(w + (size_t)S * max_B * L.R * act_e);
-        L.off_dz = w;  w = align_up(w + (size_t)S * max_B * L.R * e);
+        L.off_act = w; w = align_up(w + (size_t)S * max_B * L.ldr * act_e);
+        L.off_dz = w;  w = align_up(w + (size_t)S * max_B * L.ldr * e);
     }
+    ctx->off_zeros = w; w = align_up(w + 256);   // stays zero: source of out-of-range operand chunks
     ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)S * max_B);
     ctx->off_bitmap = w;
     if (d->input == IST_CSR)
         w = align_up(w + sizeof(uint32_t) * (size_t)S * ctx->dims[0] * ((max_B + 31) / 32));
     ctx->off_err = w; w = align_up(w + sizeof(int32_t));
+    // split-K scratch: the largest partial buffer any forward / backward-data product needs
+    size_t pmax = 0;
+    for (int l = 1; l <= t; ++l) {
+        const LayerPlan &L = ctx->layer[l - 1];
+        if (L.transposed) continue;
+        SplitPlan f = plan_gemm(max_B, (int32_t)L.R, (int32_t)L.C, S, true);
+        if (f.splits > 1) pmax = std::max(pmax, (size_t)S * f.splits * max_B * L.R * sizeof(float));
+        if (l > 1) {
+            SplitPlan b = plan_gemm(max_B, (int32_t)L.C, (int32_t)L.R, S, true);
+            if (b.splits > 1) pmax = std::max(pmax, (size_t)S * b.splits * max_B * L.C * sizeof(float));
+        }
+    }
+    ctx->off_partial = w; ctx->partial_bytes = pmax; w = align_up(w + pmax);
     ctx->workspace_bytes = w;
     *out = ctx;
     return IST_OK;
@@ -209,10 +233,12 @@ ist_status ist_profile_read(ist_ctx *ctx, int32_t cls, double *total_ms, int64_t
     double tot = 0.0;
     int64_t n = 0;
     if (!ctx->prof_recs.empty()) IST_HIP(hipEventSynchronize(ctx->prof_recs.back().stop), "profile read");
+    static const bool dump = getenv("IST_PROF_DUMP") != nullptr;   // debugging aid: one line per launch
     for (auto &r : ctx->prof_recs) {
         if (r.cls != cls) continue;
         float ms = 0.0f;
         IST_HIP(hipEventElapsedTime(&ms, r.start, r.stop), "profile read");
+        if (dump) fprintf(stderr, "ist_prof %s %.2f us\n", kClassNames[cls], ms * 1e3);
         tot += ms;
         ++n;
     }
@@ -250,7 +276,8 @@ ist_status ist_bind(ist_ctx *ctx, void *subnets, size_t sb, void *workspace, siz
     // also after a partition with an invalid permutation.
     const size_t tables = ctx->layer[0].off_W;
     IST_HIP(hipMemset(ctx->subnets, 0, tables), "ist_bind: clear tables");
-    IST_HIP(hipMemset(ctx->workspace, 0, ctx->layer[0].off_act), "ist_bind: clear scratch tables");
+    // scratch tables, and the activation / gradient buffers whose row padding must stay zero
+    IST_HIP(hipMemset(ctx->workspace, 0, ctx->off_rowloss), "ist_bind: clear workspace");
     IST_HIP(hipMemset(ctx->workspace + ctx->off_err, 0, sizeof(int32_t)), "ist_bind: clear flag");
     ctx->bound = true;
     return IST_OK;
@@ -421,21 +448,22 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             const LayerPlan &L = ctx->layer[l - 1];
             const void *bias = ctx->has_bias ? sb + L.off_b : nullptr;
             if (l == 1 && csr) {
-                CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R};
+                CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R, L.ldr};
                 IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act, dt, st), "csr forward");
                 continue;
             }
             GemmArgs a{};
+            set_split(ctx, a);
             if (l == 1) {
                 a.A = static_cast<const char *>(bt->x) + (size_t)row0 * L.C * e;
                 a.gA = bt->stride_s * L.C;
             } else {
                 a.A = ws + ctx->layer[l - 2].off_act;
-                a.gA = (int64_t)B * L.C;
+                a.gA = (int64_t)B * ctx->layer[l - 2].ldr;
             }
-            a.sam = L.C; a.sak = 1;
+            a.sam = (l == 1) ? L.C : ctx->layer[l - 2].ldr; a.sak = 1;
             a.B = sb + L.off_W; a.sbn = L.C; a.sbk = 1; a.gB = L.R * L.C;
-            a.C = ws + L.off_act; a.ldc = L.R; a.gC = (int64_t)B * L.R;
+            a.C = ws + L.off_act; a.ldc = L.ldr; a.gC = (int64_t)B * L.ldr;
             a.M = B; a.N = (int32_t)L.R; a.K = (int32_t)L.C; a.G = S;
             a.bias = bias; a.gBias = L.R;
             IST_RUN(KC_GEMM_FWD, launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
@@ -444,7 +472,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
         {
             const LayerPlan &L = ctx->layer[t - 1];
             IST_RUN(KC_SOFTMAX_XENT, launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
-                                        bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, dt, st),
+                                        bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, L.ldr, dt, st),
                     "softmax cross-entropy");
             if (loss_out) IST_RUN(KC_LOSS_REDUCE, launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
         }
@@ -454,29 +482,31 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by h_{l-1} > 0, old W_l
                 const LayerPlan &P = ctx->layer[l - 2];
                 GemmArgs a{};
-                a.A = ws + L.off_dz; a.sam = L.R; a.sak = 1; a.gA = (int64_t)B * L.R;
+                set_split(ctx, a);
+                a.A = ws + L.off_dz; a.sam = L.ldr; a.sak = 1; a.gA = (int64_t)B * L.ldr;
                 a.B = sb + L.off_W; a.sbn = 1; a.sbk = L.C; a.gB = L.R * L.C;
-                a.C = ws + P.off_dz; a.ldc = L.C; a.gC = (int64_t)B * L.C;
+                a.C = ws + P.off_dz; a.ldc = P.ldr; a.gC = (int64_t)B * P.ldr;
                 a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
-                a.mask = ws + P.off_act; a.ldm = L.C; a.gMask = (int64_t)B * L.C;
+                a.mask = ws + P.off_act; a.ldm = P.ldr; a.gMask = (int64_t)B * P.ldr;
                 IST_RUN(KC_GEMM_BWD_DATA, launch_gemm(dt, EPI_BWD_DATA, a, st), "backward-data gemm");
             }
             if (l == 1 && csr) {
-                CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R};
+                CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R, L.ldr};
                 IST_RUN(KC_CSR_UPDATE, launch_csr_update(c, sb + L.off_W, ws + L.off_dz,
                                           reinterpret_cast<uint32_t *>(ws + ctx->off_bitmap), lr, dt, st),
                         "csr update");
             } else {       // W_l <- W_l - lr * dz_l^T h_{l-1}
                 GemmArgs a{};
-                a.A = ws + L.off_dz; a.sam = 1; a.sak = L.R; a.gA = (int64_t)B * L.R;
+                set_split(ctx, a);
+                a.A = ws + L.off_dz; a.sam = 1; a.sak = L.ldr; a.gA = (int64_t)B * L.ldr;
                 if (l == 1) {
                     a.B = static_cast<const char *>(bt->x) + (size_t)row0 * L.C * e;
                     a.gB = bt->stride_s * L.C;
                 } else {
                     a.B = ws + ctx->layer[l - 2].off_act;
-                    a.gB = (int64_t)B * L.C;
+                    a.gB = (int64_t)B * ctx->layer[l - 2].ldr;
                 }
-                a.sbn = 1; a.sbk = L.C;
+                a.sbn = 1; a.sbk = (l == 1) ? L.C : ctx->layer[l - 2].ldr;
                 a.C = sb + L.off_W; a.ldc = L.C; a.gC = L.R * L.C;
                 a.M = (int32_t)L.R; a.N = (int32_t)L.C; a.K = B; a.G = S;
                 a.lr = lr;
@@ -490,7 +520,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 ba.B = B; ba.G = S; ba.lr = lr;
                 for (int l = l0; l <= t && l < l0 + kMaxBiasJobs; ++l) {
                     const LayerPlan &L = ctx->layer[l - 1];
-                    ba.job[ba.njobs++] = BiasJob{sb + L.off_b, ws + L.off_dz, L.R, 0};
+                    ba.job[ba.njobs++] = BiasJob{sb + L.off_b, ws + L.off_dz, L.R, L.ldr, 0};
                 }
                 IST_RUN(KC_BIAS_UPDATE, launch_bias_update(ba, dt, st), "bias update");
             }

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D
         acc = fmaf(D::up(vals[p]), D::ld(Wg + (int64_t)col * c.w + q), acc);
     }
     if (bias) acc += D::ld(bias + (int64_t)g * c.w + q);
-    h[((int64_t)g * c.B + b) * c.w + q] = D::cvt(acc > 0.0f ? acc : 0.0f);
+    h[((int64_t)g * c.B + b) * c.ld + q] = D::cvt(acc > 0.0f ? acc : 0.0f);
 }
 
 __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
 
     const T *vals = static_cast<const T *>(c.vals);
     T *wrow = Wt + ((int64_t)g * c.N0 + col) * c.w;
-    const T *dzg = dz + (int64_t)g * c.B * c.w;
+    const T *dzg = dz + (int64_t)g * c.B * c.ld;
     for (int64_t q0 = 0; q0 < c.w; q0 += 256) {          // 4 outputs per lane per pass
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int b0 = 0; b0 < c.B; b0 += 64) {
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
                 const int src = __ffsll((long long)m) - 1;
                 m &= m - 1;
                 const float xv = __shfl(v, src);
-                const T *dr = dzg + (int64_t)(b0 + src) * c.w + q0;
+                const T *dr = dzg + (int64_t)(b0 + src) * c.ld + q0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     int64_t q = (int64_t)i * 64 + lane;

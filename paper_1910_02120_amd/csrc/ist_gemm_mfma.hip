@@ -17,8 +17,13 @@
 // f32: v_mfma_f32_32x32x2_f32, one value per lane and operand; both LDS layouts
 // are read with plain 32-bit loads.
 //
-// 256 threads = 4 wavefronts in a 2x2 arrangement; macro tile BM x BN x 32.
-// Global loads are 16 bytes per lane, prefetched into registers one k-tile ahead.
+// Workgroup = 4*KG wavefronts: a 2x2 arrangement over the BM x BN tile, times KG
+// "k-groups" that share the LDS tiles and each take every KG-th MFMA k-step (their
+// accumulators are added through LDS in fixed order at the end).  Small problems use
+// 64x64 tiles with KG > 1 so that all SIMDs have a wave; large ones 128x128, KG = 1.
+// Global loads are 16 bytes per lane and run ST k-tiles ahead in registers.
+// The epilogue goes through LDS so that every lane owns 8 consecutive columns of a
+// row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses.
 #include "ist_internal.h"
 
 namespace ist {
@@ -53,7 +58,7 @@ template <> struct Mma<BF16> {
     }
     __device__ static inline Frag frag_m(const E *lds, int rb, int ks, int lane, int ld)
     {
-        // 16-lane block: lane q supplies the address of 4 consecutive rows-elements
+        // 16-lane block: lane q supplies the address of 4 consecutive row-elements
         // [k0 + q/4][m0 + 4*(q%4)] and receives [k0 .. k0+3][m0 + q].
         const int q = lane & 15;
         const int m0 = rb + ((lane >> 4) & 1) * 16;
@@ -95,8 +100,8 @@ template <> struct Mma<F32> {
     }
 };
 
-// One operand tile: ROWS rows (m or n) by KT k values.
-template <typename D, bool KCONTIG, int ROWS>
+// One operand tile: ROWS rows (m or n) by KT k values, loaded by NT threads.
+template <typename D, bool KCONTIG, int ROWS, int NT>
 struct Tile {
     using M = Mma<D>;
     using E = typename M::E;
@@ -104,7 +109,7 @@ struct Tile {
     static constexpr int LD = KCONTIG ? M::ld_k(ROWS) : M::ld_m(ROWS);
     static constexpr int ELEMS = KCONTIG ? ROWS * LD : KT * LD;
     static constexpr int CHUNKS = ROWS * KT / CH;
-    static constexpr int PER = (CHUNKS + 255) / 256;   // chunks per thread
+    static constexpr int PER = (CHUNKS + NT - 1) / NT;   // chunks per thread
 
     struct Regs { uint4 v[PER]; };
 
@@ -115,32 +120,34 @@ struct Tile {
         else         { k = c / (ROWS / CH); row = (c % (ROWS / CH)) * CH; }
     }
 
-    // s_row / s_k: element strides of the row index and of k (one of them is 1)
-    __device__ static inline void load(Regs &r, const E *base, int64_t s_row, int64_t s_k, int row0,
-                                       int rows_total, int k0, int K, bool vec)
+    // s_row / s_k: element strides of the row index and of k (one of them is 1).
+    // VEC: one unconditional 16-byte load per chunk; a chunk outside the operand is
+    // read from a block of zeros instead, so nothing branches around the loads, nothing
+    // has to touch the loaded registers before they are stored to LDS, and the loads
+    // stay in flight across k-tiles.
+    template <bool VEC>
+    __device__ static inline void load(Regs &r, const E *base, const E *zeros, int64_t s_row, int64_t s_k,
+                                       int row0, int rows_total, int k0, int K)
     {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int c = threadIdx.x + i * 256;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (CHUNKS % 256 == 0 || c < CHUNKS) {
-                int row, k;
-                coords(c, row, k);
-                const int gr = row0 + row, gk = k0 + k;
-                if (gr < rows_total && gk < K) {
-                    const E *p = base + (int64_t)gr * s_row + (int64_t)gk * s_k;
-                    if (vec) {
-                        v = *reinterpret_cast<const uint4 *>(p);
-                    } else {
-                        E tmp[CH];
+            const int c = threadIdx.x + i * NT;
+            int row, k;
+            coords(c, row, k);
+            const int gr = row0 + row, gk = k0 + k;
+            const bool ok = (CHUNKS % NT == 0 || c < CHUNKS) && gr < rows_total && gk < K;
+            const E *p = ok ? base + ((int64_t)gr * s_row + (int64_t)gk * s_k) : zeros;
+            uint4 v;
+            if (VEC) {
+                v = *reinterpret_cast<const uint4 *>(p);
+            } else {
+                E tmp[CH];
 #pragma unroll
-                        for (int e = 0; e < CH; ++e) {
-                            const bool ok = KCONTIG ? (gk + e < K) : (gr + e < rows_total);
-                            tmp[e] = ok ? p[e] : (E)0;
-                        }
-                        __builtin_memcpy(&v, tmp, 16);
-                    }
+                for (int e = 0; e < CH; ++e) {
+                    const bool oke = ok && (KCONTIG ? (gk + e < K) : (gr + e < rows_total));
+                    tmp[e] = (oke ? p : zeros)[oke ? e : 0];
                 }
+                __builtin_memcpy(&v, tmp, 16);
             }
             r.v[i] = v;
         }
@@ -150,8 +157,8 @@ struct Tile {
     {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int c = threadIdx.x + i * 256;
-            if (CHUNKS % 256 == 0 || c < CHUNKS) {
+            const int c = threadIdx.x + i * NT;
+            if (CHUNKS % NT == 0 || c < CHUNKS) {
                 int row, k;
                 coords(c, row, k);
                 if (KCONTIG) M::store_k(lds, row, k / CH, r.v[i], LD);
@@ -166,24 +173,141 @@ struct Tile {
     }
 };
 
-template <typename D, bool AK, bool BKC, int EPI, int BM, int BN>
-__global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, bool vecA, bool vecB)
+// ---------------------------------------------------------------- 8-wide row accesses
+template <typename T> struct Row8;
+template <> struct Row8<uint16_t> {
+    __device__ static inline void ld(const uint16_t *p, bool vec, int nv, float (&o)[8])
+    {
+        if (vec) {
+            uint4 r = *reinterpret_cast<const uint4 *>(p);
+            const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                o[2 * i] = __uint_as_float(w[i] << 16);
+                o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = i < nv ? bf16_to_f32(p[i]) : 0.0f;
+        }
+    }
+    __device__ static inline void st(uint16_t *p, bool vec, int nv, const float (&v)[8])
+    {
+        if (vec) {
+            uint32_t w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+            *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (i < nv) p[i] = f32_to_bf16(v[i]);
+        }
+    }
+};
+template <> struct Row8<float> {
+    __device__ static inline void ld(const float *p, bool vec, int nv, float (&o)[8])
+    {
+        if (vec) {
+            float4 a = *reinterpret_cast<const float4 *>(p);
+            float4 b = *reinterpret_cast<const float4 *>(p + 4);
+            o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = i < nv ? p[i] : 0.0f;
+        }
+    }
+    __device__ static inline void st(float *p, bool vec, int nv, const float (&v)[8])
+    {
+        if (vec) {
+            *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (i < nv) p[i] = v[i];
+        }
+    }
+};
+
+// Epilogue for 8 consecutive columns n0..n0+7 of row m (gz: output group index).
+template <typename D, int EPI>
+__device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, float (&val)[8], bool vecC)
+{
+    using T = typename D::T;
+    if (m >= a.M || n0 >= a.N) return;
+    const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
+    const bool vec = vecC && nv == 8;
+    const int64_t ci = (int64_t)gz * a.gC + (int64_t)m * a.ldc + n0;
+    if (EPI == EPI_PARTIAL) {
+        Row8<float>::st(static_cast<float *>(a.C) + ci, vec, nv, val);
+        return;
+    }
+    if (EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS) {
+        if (a.bias) {
+            float b[8];
+            Row8<T>::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n0, vec, nv, b);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) val[i] += b[i];
+        }
+        if (EPI == EPI_FWD_RELU) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) val[i] = val[i] > 0.0f ? val[i] : 0.0f;
+            Row8<T>::st(static_cast<T *>(a.C) + ci, vec, nv, val);
+        } else {
+            Row8<float>::st(static_cast<float *>(a.C) + ci, vec, nv, val);
+        }
+        return;
+    }
+    float o[8];
+    if (EPI == EPI_BWD_DATA) {
+        Row8<T>::ld(static_cast<const T *>(a.mask) + (int64_t)g * a.gMask + (int64_t)m * a.ldm + n0, vec, nv, o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val[i] = o[i] > 0.0f ? val[i] : 0.0f;
+    } else {   // EPI_UPDATE
+        Row8<T>::ld(static_cast<const T *>(a.C) + ci, vec, nv, o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val[i] = o[i] - a.lr * val[i];
+    }
+    Row8<T>::st(static_cast<T *>(a.C) + ci, vec, nv, val);
+}
+
+template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; };
+
+// splits > 1 (EPI_PARTIAL only): blockIdx.z = g * splits + sp and the fp32 tile of split
+// sp goes to C + (g*splits + sp) * gC; a second kernel adds the splits in order.
+template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int KG, int ST, bool VEC>
+__global__ __launch_bounds__(256 * KG) void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split)
 {
     using M = Mma<D>;
     using E = typename M::E;
-    using TA = Tile<D, AK, BM>;
-    using TB = Tile<D, BKC, BN>;
+    constexpr int NT = 256 * KG;
+    using TA = Tile<D, AK, BM, NT>;
+    using TB = Tile<D, BKC, BN, NT>;
     constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA tiles per wave
+    constexpr int LDC = 32 * TN + 4;            // staging row pitch (floats)
+    constexpr int TILE_BYTES = (TA::ELEMS + TB::ELEMS) * (int)sizeof(E);
+    constexpr int RED_BYTES = (KG - 1) * 4 * TM * TN * 16 * 64 * 4;
+    constexpr int STAGE_BYTES = 4 * 32 * LDC * 4;
+    constexpr int SMEM = MaxOf<TILE_BYTES, MaxOf<RED_BYTES, STAGE_BYTES>::v>::v;
+    static_assert(M::KSTEPS % KG == 0, "k-groups must divide the MFMA k-steps of a tile");
 
-    __shared__ __attribute__((aligned(16))) E As[TA::ELEMS];
-    __shared__ __attribute__((aligned(16))) E Bs[TB::ELEMS];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+    E *As = reinterpret_cast<E *>(smem);
+    E *Bs = As + TA::ELEMS;
 
-    const int g = blockIdx.z;
+    const int g = blockIdx.z / splits, sp = blockIdx.z % splits;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const E *A = static_cast<const E *>(a.A) + (int64_t)g * a.gA;
     const E *B = static_cast<const E *>(a.B) + (int64_t)g * a.gB;
+    const E *Z = static_cast<const E *>(a.zeros);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave & 1) * (BM / 2), wn = (wave >> 1) * (BN / 2);
+    const int w4 = wave & 3, kg = wave >> 2;
+    const int wm = (w4 & 1) * (BM / 2), wn = (w4 >> 1) * (BN / 2);
+    const int kbeg = sp * k_per_split;
+    const int kend = min(a.K, kbeg + k_per_split);
+    const int ntile = (kend - kbeg + KT - 1) / KT;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -193,21 +317,18 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, bool vecA, bool v
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    typename TA::Regs ra;
-    typename TB::Regs rb;
-    TA::load(ra, A, a.sam, a.sak, m0, a.M, 0, a.K, vecA);
-    TB::load(rb, B, a.sbn, a.sbk, n0, a.N, 0, a.K, vecB);
-
-    for (int k0 = 0; k0 < a.K; k0 += KT) {
-        TA::store(As, ra);
-        TB::store(Bs, rb);
-        __syncthreads();
-        if (k0 + KT < a.K) {
-            TA::load(ra, A, a.sam, a.sak, m0, a.M, k0 + KT, a.K, vecA);
-            TB::load(rb, B, a.sbn, a.sbk, n0, a.N, k0 + KT, a.K, vecB);
-        }
+    typename TA::Regs ra[ST];
+    typename TB::Regs rb[ST];
 #pragma unroll
-        for (int ks = 0; ks < M::KSTEPS; ++ks) {
+    for (int s = 0; s < ST; ++s) {
+        TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + s * KT, kend);
+        TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + s * KT, kend);
+    }
+
+    auto compute = [&]() {
+#pragma unroll
+        for (int q = 0; q < M::KSTEPS / KG; ++q) {
+            const int ks = q * KG + kg;
             typename M::Frag fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[i] = TA::frag(As, wm + i * 32, ks, lane);
@@ -218,68 +339,210 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, bool vecA, bool v
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = M::mma(fa[i], fb[j], acc[i][j]);
         }
+    };
+
+    // Main loop: whole groups of ST tiles, no branch around any load (loads past the
+    // end of k are masked, not skipped), so the wait counters stay exact.
+    int it0 = 0;
+    for (; it0 + ST <= ntile; it0 += ST) {
+#pragma unroll
+        for (int s = 0; s < ST; ++s) {
+            TA::store(As, ra[s]);
+            TB::store(Bs, rb[s]);
+            __syncthreads();
+            TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it0 + s + ST) * KT, kend);
+            TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it0 + s + ST) * KT, kend);
+            compute();
+            __syncthreads();
+        }
+    }
+    // Tail: the last ntile % ST tiles are already in registers.
+    const int rem = ntile - it0;
+#pragma unroll
+    for (int s = 0; s < ST; ++s) {
+        if (s < rem) {
+            TA::store(As, ra[s]);
+            TB::store(Bs, rb[s]);
+            __syncthreads();
+            compute();
+            __syncthreads();
+        }
+    }
+
+    // ---- add the k-groups' accumulators (fixed order kg = 1, 2, ...) ----
+    float *fsm = reinterpret_cast<float *>(smem);
+    if (KG > 1) {
+        if (kg > 0) {
+            float *dst = fsm + (size_t)((kg - 1) * 4 + w4) * (TM * TN * 16 * 64);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (kg == 0) {
+            for (int g2 = 1; g2 < KG; ++g2) {
+                const float *src = fsm + (size_t)((g2 - 1) * 4 + w4) * (TM * TN * 16 * 64);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
+            }
+        }
         __syncthreads();
     }
 
-    // ---------------- epilogue ----------------
-    using T = typename D::T;
+    // ---- epilogue through LDS: each lane gets 8 consecutive columns of one row ----
+    float *stage = fsm + w4 * (32 * LDC);
+    constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
+    constexpr int RPP = 64 / CPR;      // rows per pass
+    const int gz = blockIdx.z;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        if (i > 0) __syncthreads();
+        if (kg == 0) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn + j * 32 + (lane & 31);
-            if (n >= a.N) continue;
-            float bias = 0.0f;
-            if ((EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS) && a.bias)
-                bias = D::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n);
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (m >= a.M) continue;
-                float val = acc[i][j][v];
-                const int64_t ci = (int64_t)g * a.gC + (int64_t)m * a.ldc + n;
-                if (EPI == EPI_FWD_RELU) {
-                    val += bias;
-                    static_cast<T *>(a.C)[ci] = D::cvt(val > 0.0f ? val : 0.0f);
-                } else if (EPI == EPI_FWD_LOGITS) {
-                    static_cast<float *>(a.C)[ci] = val + bias;
-                } else if (EPI == EPI_BWD_DATA) {
-                    float h = D::ld(static_cast<const T *>(a.mask) + (int64_t)g * a.gMask + (int64_t)m * a.ldm + n);
-                    static_cast<T *>(a.C)[ci] = D::cvt(h > 0.0f ? val : 0.0f);
-                } else {
-                    T *w = static_cast<T *>(a.C) + ci;
-                    *w = D::cvt(D::up(*w) - a.lr * val);
-                }
+                for (int v = 0; v < 16; ++v)
+                    stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * LDC + 32 * j + (lane & 31)] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+            for (int p = 0; p < 32 / RPP; ++p) {
+                const int row = p * RPP + lane / CPR, ch = lane % CPR;
+                const float4 x = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch);
+                const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
+                float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+                epi8<D, EPI>(a, g, EPI == EPI_PARTIAL ? gz : g, m0 + wm + i * 32 + row, n0 + wn + 8 * ch, val, vecC);
             }
         }
     }
 }
 
-// 16-byte loads need: aligned base and group stride, contiguous extent and the
-// strided pitch multiples of the chunk size.
-static bool vec_ok(const void *base, int64_t gstride, int64_t pitch, int64_t extent, int esz)
+// out[g][m][n] = epilogue(sum_sp partial[g*splits + sp][m][n]) for split-K launches.
+template <typename D, int EPI>
+__global__ __launch_bounds__(256) void k_splitk_finish(GemmArgs a, const float *__restrict__ partial,
+                                                       int splits, bool vecC)
+{
+    const int g = blockIdx.z;
+    const int chunks_per_row = (a.N + 7) / 8;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)a.M * chunks_per_row) return;
+    const int m = (int)(idx / chunks_per_row), n0 = (int)(idx % chunks_per_row) * 8;
+    const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
+    const int64_t mn = (int64_t)a.M * a.N;
+    const bool pvec = (a.N % 4 == 0) && nv == 8;
+    float val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int sp = 0; sp < splits; ++sp) {
+        float t[8];
+        Row8<float>::ld(partial + ((int64_t)g * splits + sp) * mn + (int64_t)m * a.N + n0, pvec, nv, t);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val[i] += t[i];
+    }
+    epi8<D, EPI>(a, g, g, m, n0, val, vecC);
+}
+
+// 16-byte loads need an aligned base and group stride and a pitch that is a multiple
+// of the chunk size.  The contiguous extent may end inside a chunk when the pitch is
+// padded: along m/n the extra elements only feed output rows/columns that the epilogue
+// drops, along k the padding of the library's own buffers is kept at zero.
+static bool vec_ok(const void *base, int64_t gstride, int64_t pitch, int esz)
 {
     const int ch = 16 / esz;
-    return reinterpret_cast<uintptr_t>(base) % 16 == 0 && gstride % ch == 0 && pitch % ch == 0 &&
-           extent % ch == 0;
+    return reinterpret_cast<uintptr_t>(base) % 16 == 0 && gstride % ch == 0 && pitch % ch == 0;
+}
+
+static bool vec_c_ok(const GemmArgs &a, int epi, int esz)
+{
+    const int out_esz = (epi == EPI_FWD_LOGITS || epi == EPI_PARTIAL) ? 4 : esz;
+    const int ch = 16 / out_esz;
+    bool ok = reinterpret_cast<uintptr_t>(a.C) % 16 == 0 && a.gC % ch == 0 && a.ldc % ch == 0;
+    const int che = 16 / esz;
+    if ((epi == EPI_FWD_RELU || epi == EPI_FWD_LOGITS) && a.bias)
+        ok = ok && reinterpret_cast<uintptr_t>(a.bias) % 16 == 0 && a.gBias % che == 0;
+    if (epi == EPI_BWD_DATA)
+        ok = ok && reinterpret_cast<uintptr_t>(a.mask) % 16 == 0 && a.gMask % che == 0 && a.ldm % che == 0;
+    return ok;
+}
+
+// Tile size and split-K plan as a function of the problem shape only, so that the
+// workspace can be sized when the context is created.  Splitting k over workgroups
+// costs a second kernel, so it is kept for products with a very long k and few tiles
+// (the backward-data product of a very wide output layer).
+SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split)
+{
+    SplitPlan p{};
+    const int64_t big_tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * G;
+    if (big_tiles >= 1024 && M > 64 && N > 64) {
+        p.tile = 128; p.splits = 1; p.k_per_split = K; p.tiles = big_tiles;
+        return p;
+    }
+    p.tile = 64;
+    p.tiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * G;
+    int splits = 1;
+    if (allow_split && p.tiles <= 256 && K >= 16384) {
+        const int64_t want = 4096 / p.tiles;          // aim at ~4096 workgroups
+        const int64_t most = K / (16 * KT);           // at least 16 k-tiles per split
+        splits = (int)(want < most ? want : most);
+        if (splits < 1) splits = 1;
+    }
+    int kps = ((K + splits - 1) / splits + KT - 1) / KT * KT;
+    if (kps < KT) kps = KT;
+    splits = (K + kps - 1) / kps;
+    p.splits = splits; p.k_per_split = kps;
+    return p;
+}
+
+template <typename D> struct SmallCfg;
+template <> struct SmallCfg<F32> { static constexpr int KG = 4; };
+template <> struct SmallCfg<BF16> { static constexpr int KG = 2; };
+
+template <typename D, bool AK, bool BKC, int EPI, bool VEC>
+static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
+{
+    const int esz = D::kBytes;
+    const bool vecC = vec_c_ok(a, EPI, esz);
+    const bool can_split = EPI != EPI_UPDATE && a.partial != nullptr;
+    SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split);
+    if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes) {
+        p.splits = 1; p.k_per_split = a.K;
+    }
+    constexpr int KG = SmallCfg<D>::KG;
+    if (p.tile == 128) {
+        dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128), (unsigned)a.G);
+        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 1, 2, VEC>), grid, dim3(256), 0, st, a, vecC, 1,
+                           a.K);
+    } else if (p.splits == 1) {
+        dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)a.G);
+        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 64, 64, KG, 3, VEC>), grid, dim3(256 * KG), 0, st, a, vecC,
+                           1, a.K);
+    } else {
+        GemmArgs pa = a;
+        pa.C = a.partial; pa.ldc = a.N; pa.gC = (int64_t)a.M * a.N;
+        const bool vecP = vec_c_ok(pa, EPI_PARTIAL, esz);
+        dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)(a.G * p.splits));
+        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI_PARTIAL, 64, 64, KG, 3, VEC>), grid, dim3(256 * KG), 0, st,
+                           pa, vecP, p.splits, p.k_per_split);
+        const int64_t units = (int64_t)a.M * ((a.N + 7) / 8);
+        dim3 g2((unsigned)((units + 255) / 256), 1, (unsigned)a.G);
+        hipLaunchKernelGGL((k_splitk_finish<D, EPI>), g2, dim3(256), 0, st, a, a.partial, p.splits, vecC);
+    }
+    return hipGetLastError();
 }
 
 template <typename D, bool AK, bool BKC, int EPI>
 static hipError_t launch_cfg(const GemmArgs &a, hipStream_t st)
 {
     const int esz = D::kBytes;
-    // A: K-contig -> pitch sam, extent K; M-contig -> pitch sak, extent M
-    const bool vecA = AK ? vec_ok(a.A, a.gA, a.sam, a.K, esz) : vec_ok(a.A, a.gA, a.sak, a.M, esz);
-    const bool vecB = BKC ? vec_ok(a.B, a.gB, a.sbn, a.K, esz) : vec_ok(a.B, a.gB, a.sbk, a.N, esz);
-    const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.G;
-    if (big_tiles >= 192 && a.M > 64 && a.N > 64) {
-        dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128), (unsigned)a.G);
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 128, 128>), grid, dim3(256), 0, st, a, vecA, vecB);
-    } else {
-        dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)a.G);
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 64, 64>), grid, dim3(256), 0, st, a, vecA, vecB);
-    }
-    return hipGetLastError();
+    const bool vecA = vec_ok(a.A, a.gA, AK ? a.sam : a.sak, esz);
+    const bool vecB = vec_ok(a.B, a.gB, BKC ? a.sbn : a.sbk, esz);
+    return (vecA && vecB) ? launch_vec<D, AK, BKC, EPI, true>(a, st) : launch_vec<D, AK, BKC, EPI, false>(a, st);
 }
 
 template <typename D>
@@ -309,7 +572,7 @@ static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0 || a.G <= 0) return hipSuccess;
-    if ((a.M + 63) / 64 > 65535) return hipErrorInvalidValue;
+    if ((a.M + 63) / 64 > 65535 || a.zeros == nullptr) return hipErrorInvalidValue;
     return dtype == IST_BF16 ? launch_dtype<BF16>(epi, a, st) : launch_dtype<F32>(epi, a, st);
 }
 

@@ -44,6 +44,7 @@ struct BF16 {
 struct LayerPlan {           // weight matrix l = 1..t
     int64_t N_out = 0, N_in = 0;   // full sizes N_l, N_{l-1}
     int64_t R = 0, C = 0;          // rows/cols held by one subnet
+    int64_t ldr = 0;               // row pitch of the [B][R] activation / gradient buffers (R rounded up to 8)
     bool row_part = false;         // rows follow the blocks of hidden layer l
     bool col_part = false;         // cols follow the blocks of hidden layer l-1
     bool transposed = false;       // stored [S][C][R] (sparse-input first layer)
@@ -69,6 +70,7 @@ struct ist_ctx {
     std::vector<ist::HiddenPlan> hidden;  // index l-1, l = 1..t-1
     size_t subnets_bytes = 0, workspace_bytes = 0;
     size_t off_rowloss = 0, off_bitmap = 0, off_err = 0;  // workspace
+    size_t off_partial = 0, partial_bytes = 0, off_zeros = 0;
     char *subnets = nullptr;
     char *workspace = nullptr;
     bool bound = false, partitioned = false;
@@ -124,7 +126,7 @@ hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc,
                          int64_t base_c, bool transposed, int esz, hipStream_t st);
 
 // ----------------------------------------------------------------- training
-enum Epilogue { EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3 };
+enum Epilogue { EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3, EPI_PARTIAL = 4 };
 
 // C[g][m][n] (+)= sum_k A_g(m,k) * B_g(n,k), element (m,k) of A at A + g*gA + m*sam + k*sak.
 struct GemmArgs {
@@ -135,17 +137,21 @@ struct GemmArgs {
     const void *bias; int64_t gBias;          // EPI_FWD_*: bias[n] (may be null)
     const void *mask; int64_t ldm, gMask;     // EPI_BWD_DATA: keep where mask[m][n] > 0
     float lr;                                 // EPI_UPDATE: C = C - lr * acc
+    float *partial; size_t partial_bytes;     // split-K scratch (fp32 partial products), may be null
+    const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
 };
+struct SplitPlan { int tile; int splits; int k_per_split; int64_t tiles; };
+SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split);
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
-                               int dtype, hipStream_t st);
+                               int64_t ld, int dtype, hipStream_t st);
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
                               int32_t G, int32_t B, hipStream_t st);
-struct BiasJob { void *bias; const void *dz; int64_t R; int32_t blk0; };
+struct BiasJob { void *bias; const void *dz; int64_t R, ld; int32_t blk0; };
 constexpr int kMaxBiasJobs = 16;
 struct BiasArgs { BiasJob job[kMaxBiasJobs]; int32_t njobs, B, G; float lr; };
 hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st);
@@ -155,6 +161,7 @@ struct CsrArgs {
     const int32_t *rowptr, *colidx; const void *vals; int64_t nnz;
     int64_t row0, stride_g;   // sample b of group g is CSR row row0 + g*stride_g + b
     int32_t G, B; int64_t N0, w;
+    int64_t ld;               // row pitch of h_1 / dz_1
 };
 hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h,
                               int dtype, hipStream_t st);

@@ -39,12 +39,12 @@ __global__ __launch_bounds__(NT) void k_softmax_xent(const float *__restrict__ l
                                                      int64_t y_stride_g,
                                                      typename D::T *__restrict__ dz,
                                                      float *__restrict__ rowloss, int32_t B,
-                                                     int64_t Cn)
+                                                     int64_t Cn, int64_t ld)
 {
     __shared__ float sh[NT / 64];
     const int g = blockIdx.y, b = blockIdx.x;
-    const float *z = logits + ((int64_t)g * B + b) * Cn;
-    typename D::T *out = dz + ((int64_t)g * B + b) * Cn;
+    const float *z = logits + ((int64_t)g * B + b) * ld;
+    typename D::T *out = dz + ((int64_t)g * B + b) * ld;
     float mx = -INFINITY;
     for (int64_t c = threadIdx.x; c < Cn; c += NT) mx = fmaxf(mx, z[c]);
     mx = block_reduce<NT>(mx, sh, true);
@@ -65,24 +65,24 @@ __global__ __launch_bounds__(NT) void k_softmax_xent(const float *__restrict__ l
 }
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g, void *dz,
-                               float *rowloss, int32_t G, int32_t B, int64_t Cn, int dtype,
+                               float *rowloss, int32_t G, int32_t B, int64_t Cn, int64_t ld, int dtype,
                                hipStream_t st)
 {
     dim3 grid((unsigned)B, (unsigned)G);
     if (Cn <= 256) {
         if (dtype == IST_BF16)
             hipLaunchKernelGGL((k_softmax_xent<BF16, 64>), grid, dim3(64), 0, st, logits, y, y_stride_g,
-                               (uint16_t *)dz, rowloss, B, Cn);
+                               (uint16_t *)dz, rowloss, B, Cn, ld);
         else
             hipLaunchKernelGGL((k_softmax_xent<F32, 64>), grid, dim3(64), 0, st, logits, y, y_stride_g,
-                               (float *)dz, rowloss, B, Cn);
+                               (float *)dz, rowloss, B, Cn, ld);
     } else {
         if (dtype == IST_BF16)
             hipLaunchKernelGGL((k_softmax_xent<BF16, 1024>), grid, dim3(1024), 0, st, logits, y,
-                               y_stride_g, (uint16_t *)dz, rowloss, B, Cn);
+                               y_stride_g, (uint16_t *)dz, rowloss, B, Cn, ld);
         else
             hipLaunchKernelGGL((k_softmax_xent<F32, 1024>), grid, dim3(1024), 0, st, logits, y,
-                               y_stride_g, (float *)dz, rowloss, B, Cn);
+                               y_stride_g, (float *)dz, rowloss, B, Cn, ld);
     }
     return hipGetLastError();
 }
@@ -122,8 +122,8 @@ __global__ __launch_bounds__(256) void k_bias_update(BiasArgs a)
     const int64_t r = (int64_t)(blockIdx.x - jb.blk0) * 64 + lane;
     float acc = 0.0f;
     if (r < jb.R) {
-        const T *p = static_cast<const T *>(jb.dz) + (int64_t)g * a.B * jb.R + r;
-        for (int b = wave; b < a.B; b += 4) acc += D::ld(p + (int64_t)b * jb.R);
+        const T *p = static_cast<const T *>(jb.dz) + (int64_t)g * a.B * jb.ld + r;
+        for (int b = wave; b < a.B; b += 4) acc += D::ld(p + (int64_t)b * jb.ld);
     }
     part[wave][lane] = acc;
     __syncthreads();
