@@ -23,7 +23,8 @@ def sources():
 
 def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
+    extra = os.environ.get("IST_EXTRA_FLAGS", "").split()
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
            "-o", LIB + ".tmp", *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -184,10 +184,10 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
         if (L.transposed) continue;
-        SplitPlan f = plan_gemm(max_B, (int32_t)L.R, (int32_t)L.C, S, true);
+        SplitPlan f = plan_gemm(max_B, (int32_t)L.R, (int32_t)L.C, S, true, e);
         if (f.splits > 1) pmax = std::max(pmax, (size_t)S * f.splits * max_B * L.R * sizeof(float));
         if (l > 1) {
-            SplitPlan b = plan_gemm(max_B, (int32_t)L.C, (int32_t)L.R, S, true);
+            SplitPlan b = plan_gemm(max_B, (int32_t)L.C, (int32_t)L.R, S, true, e);
             if (b.splits > 1) pmax = std::max(pmax, (size_t)S * b.splits * max_B * L.C * sizeof(float));
         }
     }

@@ -33,17 +33,17 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int KT = 32;   // k extent of one LDS tile
+template <typename D, int KT> struct Mma;   // KT: k extent of one LDS tile
 
-template <typename D> struct Mma;
-
-template <> struct Mma<BF16> {
+template <int KT> struct Mma<BF16, KT> {
     using E = uint16_t;
     using Frag = bf16x8;
     static constexpr int CH = 8;          // elements per 16-byte chunk
     static constexpr int KSTEPS = KT / 16;
     static constexpr int ld_k(int) { return KT + 8; }          // [row][k] row pitch (elements)
-    static constexpr int ld_m(int rows) { return rows + 16; }  // [k][row] row pitch
+    // [k][row] row pitch: +32 elements (16 words) keeps the four k-rows one transposing
+    // read touches in distinct bank groups (measured: SQ_LDS_BANK_CONFLICT drops ~10x vs +16)
+    static constexpr int ld_m(int rows) { return rows + 32; }
     __device__ static inline f32x16 mma(Frag a, Frag b, f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -73,7 +73,7 @@ template <> struct Mma<BF16> {
     }
 };
 
-template <> struct Mma<F32> {
+template <int KT> struct Mma<F32, KT> {
     using E = float;
     using Frag = float;
     static constexpr int CH = 4;
@@ -101,9 +101,9 @@ template <> struct Mma<F32> {
 };
 
 // One operand tile: ROWS rows (m or n) by KT k values, loaded by NT threads.
-template <typename D, bool KCONTIG, int ROWS, int NT>
+template <typename D, bool KCONTIG, int ROWS, int NT, int KT>
 struct Tile {
-    using M = Mma<D>;
+    using M = Mma<D, KT>;
     using E = typename M::E;
     static constexpr int CH = M::CH;
     static constexpr int LD = KCONTIG ? M::ld_k(ROWS) : M::ld_m(ROWS);
@@ -277,14 +277,14 @@ template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; }
 
 // splits > 1 (EPI_PARTIAL only): blockIdx.z = g * splits + sp and the fp32 tile of split
 // sp goes to C + (g*splits + sp) * gC; a second kernel adds the splits in order.
-template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int KG, int ST, bool VEC>
+template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int KG, int ST, bool VEC, int KT>
 __global__ __launch_bounds__(256 * KG) void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split)
 {
-    using M = Mma<D>;
+    using M = Mma<D, KT>;
     using E = typename M::E;
     constexpr int NT = 256 * KG;
-    using TA = Tile<D, AK, BM, NT>;
-    using TB = Tile<D, BKC, BN, NT>;
+    using TA = Tile<D, AK, BM, NT, KT>;
+    using TB = Tile<D, BKC, BN, NT, KT>;
     constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA tiles per wave
     constexpr int LDC = 32 * TN + 4;            // staging row pitch (floats)
     constexpr int TILE_BYTES = (TA::ELEMS + TB::ELEMS) * (int)sizeof(E);
@@ -475,11 +475,14 @@ static bool vec_c_ok(const GemmArgs &a, int epi, int esz)
 // workspace can be sized when the context is created.  Splitting k over workgroups
 // costs a second kernel, so it is kept for products with a very long k and few tiles
 // (the backward-data product of a very wide output layer).
-SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split)
+SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz)
 {
+    constexpr int KT = 128;   // split boundaries are multiples of every k-tile size in use
     SplitPlan p{};
     const int64_t big_tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * G;
-    if (big_tiles >= 1024 && M > 64 && N > 64) {
+    // bf16 MFMAs are fast enough that the larger tile wins as soon as it fills the chip once;
+    // f32 MFMAs are slow, there more and smaller workgroups spread the work better
+    if (big_tiles >= (esz == 2 ? 256 : 1024) && M > 64 && N > 64) {
         p.tile = 128; p.splits = 1; p.k_per_split = K; p.tiles = big_tiles;
         return p;
     }
@@ -499,9 +502,11 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
     return p;
 }
 
-template <typename D> struct SmallCfg;
-template <> struct SmallCfg<F32> { static constexpr int KG = 4; };
-template <> struct SmallCfg<BF16> { static constexpr int KG = 2; };
+// Per-dtype tile parameters: k-tile of the large (128x128) and small (64x64) configuration
+// and the number of k-groups of the small one.
+template <typename D> struct Cfg;
+template <> struct Cfg<F32> { static constexpr int KG = 4, KT_SMALL = 32, KT_BIG = 32, ST_BIG = 2; };
+template <> struct Cfg<BF16> { static constexpr int KG = 2, KT_SMALL = 32, KT_BIG = 64, ST_BIG = 1; };
 
 template <typename D, bool AK, bool BKC, int EPI, bool VEC>
 static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
@@ -509,25 +514,25 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
     const int esz = D::kBytes;
     const bool vecC = vec_c_ok(a, EPI, esz);
     const bool can_split = EPI != EPI_UPDATE && a.partial != nullptr;
-    SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split);
+    SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
     if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes) {
         p.splits = 1; p.k_per_split = a.K;
     }
-    constexpr int KG = SmallCfg<D>::KG;
+    constexpr int KG = Cfg<D>::KG, KTS = Cfg<D>::KT_SMALL, KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
     if (p.tile == 128) {
         dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128), (unsigned)a.G);
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 1, 2, VEC>), grid, dim3(256), 0, st, a, vecC, 1,
+        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 1, STB, VEC, KTB>), grid, dim3(256), 0, st, a, vecC, 1,
                            a.K);
     } else if (p.splits == 1) {
         dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)a.G);
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 64, 64, KG, 3, VEC>), grid, dim3(256 * KG), 0, st, a, vecC,
+        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 64, 64, KG, 3, VEC, KTS>), grid, dim3(256 * KG), 0, st, a, vecC,
                            1, a.K);
     } else {
         GemmArgs pa = a;
         pa.C = a.partial; pa.ldc = a.N; pa.gC = (int64_t)a.M * a.N;
         const bool vecP = vec_c_ok(pa, EPI_PARTIAL, esz);
         dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)(a.G * p.splits));
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI_PARTIAL, 64, 64, KG, 3, VEC>), grid, dim3(256 * KG), 0, st,
+        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI_PARTIAL, 64, 64, KG, 3, VEC, KTS>), grid, dim3(256 * KG), 0, st,
                            pa, vecP, p.splits, p.k_per_split);
         const int64_t units = (int64_t)a.M * ((a.N + 7) / 8);
         dim3 g2((unsigned)((units + 255) / 256), 1, (unsigned)a.G);

@@ -141,7 +141,7 @@ struct GemmArgs {
     const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
 };
 struct SplitPlan { int tile; int splits; int k_per_split; int64_t tiles; };
-SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split);
+SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz);
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
