@@ -97,6 +97,9 @@ CopyArgs copy_args(const ist_ctx *ctx, int l, void *Wfull)
     a.rows = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_sorted) : nullptr;
     a.cols = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_sorted) : nullptr;
     a.slotc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_slot) : nullptr;
+    a.maskc = L.col_part ? reinterpret_cast<const uint32_t *>(ctx->subnets + ctx->hidden[l - 2].off_mask) : nullptr;
+    a.rankc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_rank) : nullptr;
+    a.wordsc = L.col_part ? ctx->hidden[l - 2].words : 0;
     a.nr = L.R;
     a.nc = L.C;
     a.N_out = L.N_out;
@@ -144,6 +147,9 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         h.off_sorted = off; off = align_up(off + sizeof(int32_t) * h.N);
         h.off_slot = off;   off = align_up(off + sizeof(int32_t) * h.N);
         h.off_p2q = off;    off = align_up(off + sizeof(int32_t) * h.N);
+        h.words = (h.N + 31) / 32;
+        h.off_mask = off;   off = align_up(off + sizeof(uint32_t) * S * h.words);
+        h.off_rank = off;   off = align_up(off + sizeof(int32_t) * S * h.words);
     }
     const size_t tables_end = off;
     ctx->layer.resize(t);
@@ -338,6 +344,8 @@ ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *
                                    reinterpret_cast<int32_t *>(ctx->subnets + h.off_sorted),
                                    reinterpret_cast<int32_t *>(ctx->subnets + h.off_slot),
                                    reinterpret_cast<int32_t *>(ctx->subnets + h.off_p2q),
+                                   reinterpret_cast<uint32_t *>(ctx->subnets + h.off_mask),
+                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_rank),
                                    ctx->errflag(), st), "perm tables");
         if (ctx->checked)
             IST_RUN(KC_PERM_TABLES, launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");

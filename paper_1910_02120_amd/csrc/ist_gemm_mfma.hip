@@ -275,21 +275,29 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
 
 template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; };
 
-// splits > 1 (EPI_PARTIAL only): blockIdx.z = g * splits + sp and the fp32 tile of split
-// sp goes to C + (g*splits + sp) * gC; a second kernel adds the splits in order.
-template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int KG, int ST, bool VEC, int KT>
-__global__ __launch_bounds__(256 * KG) void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split)
+// splits > 1 (EPI_PARTIAL only): the fp32 tile of split sp of group g goes to
+// C + (g*splits + sp) * gC; a second kernel adds the splits in order.
+// WM x WN wavefronts tile the BM x BN block, KG k-groups share it: 64*WM*WN*KG threads.
+template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
+          bool PERSIST = (EPI == EPI_UPDATE)>
+__global__ __launch_bounds__(64 * WM * WN * KG,
+                             // waves per SIMD the register allocator must leave room for: 2 for the
+                             // 128x64 wave tile (128 accumulator registers), 3 for the 64x64 one (bf16 kernels)
+                             (D::kBytes != 2) ? 1 : ((BM / (32 * WM)) * (BN / (32 * WN)) >= 8) ? 2 : ((KG == 1 && BM >= 128) ? 3 : 1))
+void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
+                                                                 int tiles_x, int tiles_y)
 {
     using M = Mma<D, KT>;
     using E = typename M::E;
-    constexpr int NT = 256 * KG;
+    constexpr int WQ = WM * WN;
+    constexpr int NT = 64 * WQ * KG;
     using TA = Tile<D, AK, BM, NT, KT>;
     using TB = Tile<D, BKC, BN, NT, KT>;
-    constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 MFMA tiles per wave
+    constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);   // 32x32 MFMA tiles per wave
     constexpr int LDC = 32 * TN + 4;            // staging row pitch (floats)
     constexpr int TILE_BYTES = (TA::ELEMS + TB::ELEMS) * (int)sizeof(E);
-    constexpr int RED_BYTES = (KG - 1) * 4 * TM * TN * 16 * 64 * 4;
-    constexpr int STAGE_BYTES = 4 * 32 * LDC * 4;
+    constexpr int RED_BYTES = (KG - 1) * WQ * TM * TN * 16 * 64 * 4;
+    constexpr int STAGE_BYTES = WQ * 32 * LDC * 4;
     constexpr int SMEM = MaxOf<TILE_BYTES, MaxOf<RED_BYTES, STAGE_BYTES>::v>::v;
     static_assert(M::KSTEPS % KG == 0, "k-groups must divide the MFMA k-steps of a tile");
 
@@ -297,34 +305,44 @@ __global__ __launch_bounds__(256 * KG) void k_gemm_mfma(GemmArgs a, bool vecC, i
     E *As = reinterpret_cast<E *>(smem);
     E *Bs = As + TA::ELEMS;
 
-    const int g = blockIdx.z / splits, sp = blockIdx.z % splits;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const E *A = static_cast<const E *>(a.A) + (int64_t)g * a.gA;
-    const E *B = static_cast<const E *>(a.B) + (int64_t)g * a.gB;
     const E *Z = static_cast<const E *>(a.zeros);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int w4 = wave & 3, kg = wave >> 2;
-    const int wm = (w4 & 1) * (BM / 2), wn = (w4 >> 1) * (BN / 2);
-    const int kbeg = sp * k_per_split;
-    const int kend = min(a.K, kbeg + k_per_split);
-    const int ntile = (kend - kbeg + KT - 1) / KT;
+    const int w4 = wave % WQ, kg = wave / WQ;   // position in the block tile, k-group
+    const int wm = (w4 % WM) * (BM / WM), wn = (w4 / WM) * (BN / WN);
+    float *fsm = reinterpret_cast<float *>(smem);
+
+    // Block tiles are numbered n-fastest, then m, then (group, split); a workgroup takes
+    // tiles t = blockIdx.x, blockIdx.x + gridDim.x, ... and issues the first loads of its
+    // next tile before the epilogue of the current one.
+    const int per_z = tiles_x * tiles_y;
+    const int total = per_z * a.G * splits;
+    int t = blockIdx.x;
+    int g, gz, m0, n0, kbeg, kend;
+    const E *A, *B;
+    auto decode = [&](int tt) {
+        gz = tt / per_z;
+        const int r = tt - gz * per_z;
+        g = gz / splits;
+        const int sp = gz - g * splits;
+        m0 = (r / tiles_x) * BM;
+        n0 = (r % tiles_x) * BN;
+        kbeg = sp * k_per_split;
+        kend = min(a.K, kbeg + k_per_split);
+        A = static_cast<const E *>(a.A) + (int64_t)g * a.gA;
+        B = static_cast<const E *>(a.B) + (int64_t)g * a.gB;
+    };
+    decode(t);
 
     f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
     typename TA::Regs ra[ST];
     typename TB::Regs rb[ST];
+    auto prologue = [&]() {
 #pragma unroll
-    for (int s = 0; s < ST; ++s) {
-        TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + s * KT, kend);
-        TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + s * KT, kend);
-    }
-
+        for (int s = 0; s < ST; ++s) {
+            TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + s * KT, kend);
+            TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + s * KT, kend);
+        }
+    };
     auto compute = [&]() {
 #pragma unroll
         for (int q = 0; q < M::KSTEPS / KG; ++q) {
@@ -340,88 +358,112 @@ __global__ __launch_bounds__(256 * KG) void k_gemm_mfma(GemmArgs a, bool vecC, i
                 for (int j = 0; j < TN; ++j) acc[i][j] = M::mma(fa[i], fb[j], acc[i][j]);
         }
     };
+    prologue();
 
-    // Main loop: whole groups of ST tiles, no branch around any load (loads past the
-    // end of k are masked, not skipped), so the wait counters stay exact.
-    int it0 = 0;
-    for (; it0 + ST <= ntile; it0 += ST) {
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        const int ntile = (kend - kbeg + KT - 1) / KT;
+
+        // Main loop: whole groups of ST tiles, no branch around any load (loads past the
+        // end of k are masked, not skipped), so the wait counters stay exact.
+        int it0 = 0;
+        for (; it0 + ST <= ntile; it0 += ST) {
+#pragma unroll
+            for (int s = 0; s < ST; ++s) {
+                TA::store(As, ra[s]);
+                TB::store(Bs, rb[s]);
+                __syncthreads();
+                TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it0 + s + ST) * KT, kend);
+                TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it0 + s + ST) * KT, kend);
+                __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the MFMAs it overlaps with
+                compute();
+                __syncthreads();
+            }
+        }
+        // Tail: the last ntile % ST tiles are already in registers.
+        const int rem = ntile - it0;
 #pragma unroll
         for (int s = 0; s < ST; ++s) {
-            TA::store(As, ra[s]);
-            TB::store(Bs, rb[s]);
-            __syncthreads();
-            TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it0 + s + ST) * KT, kend);
-            TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it0 + s + ST) * KT, kend);
-            compute();
-            __syncthreads();
+            if (s < rem) {
+                TA::store(As, ra[s]);
+                TB::store(Bs, rb[s]);
+                __syncthreads();
+                compute();
+                __syncthreads();
+            }
         }
-    }
-    // Tail: the last ntile % ST tiles are already in registers.
-    const int rem = ntile - it0;
-#pragma unroll
-    for (int s = 0; s < ST; ++s) {
-        if (s < rem) {
-            TA::store(As, ra[s]);
-            TB::store(Bs, rb[s]);
-            __syncthreads();
-            compute();
-            __syncthreads();
-        }
-    }
 
-    // ---- add the k-groups' accumulators (fixed order kg = 1, 2, ...) ----
-    float *fsm = reinterpret_cast<float *>(smem);
-    if (KG > 1) {
-        if (kg > 0) {
-            float *dst = fsm + (size_t)((kg - 1) * 4 + w4) * (TM * TN * 16 * 64);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
-        }
-        __syncthreads();
-        if (kg == 0) {
-            for (int g2 = 1; g2 < KG; ++g2) {
-                const float *src = fsm + (size_t)((g2 - 1) * 4 + w4) * (TM * TN * 16 * 64);
+        // ---- add the k-groups' accumulators (fixed order kg = 1, 2, ...) ----
+        if (KG > 1) {
+            if (kg > 0) {
+                float *dst = fsm + (size_t)((kg - 1) * WQ + w4) * (TM * TN * 16 * 64);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
+                        for (int v = 0; v < 16; ++v) dst[((i * TN + j) * 16 + v) * 64 + lane] = acc[i][j][v];
             }
+            __syncthreads();
+            if (kg == 0) {
+                for (int g2 = 1; g2 < KG; ++g2) {
+                    const float *src = fsm + (size_t)((g2 - 1) * WQ + w4) * (TM * TN * 16 * 64);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * TN + j) * 16 + v) * 64 + lane];
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
-    }
 
-    // ---- epilogue through LDS: each lane gets 8 consecutive columns of one row ----
-    float *stage = fsm + w4 * (32 * LDC);
-    constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
-    constexpr int RPP = 64 / CPR;      // rows per pass
-    const int gz = blockIdx.z;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        if (i > 0) __syncthreads();
-        if (kg == 0) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * LDC + 32 * j + (lane & 31)] = acc[i][j][v];
+        // ---- first loads of the next tile, so that they fly during this epilogue ----
+        // (only where workgroups walk several tiles: the extra live state costs registers)
+        const int cg = g, cgz = gz, cm0 = m0, cn0 = n0;
+        const int tn = t + (int)gridDim.x;
+        const bool more = PERSIST && tn < total;
+        if (PERSIST) {
+            decode(more ? tn : t);   // unconditional (a last tile re-reads its own first k-tile):
+            prologue();              // a branch around loads would force the loop to drain them
         }
-        __syncthreads();
-        if (kg == 0) {
+
+        // ---- epilogue through LDS: each lane gets 8 consecutive columns of one row ----
+        float *stage = fsm + w4 * (32 * LDC);
+        constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
+        constexpr int RPP = 64 / CPR;      // rows per pass
 #pragma unroll
-            for (int p = 0; p < 32 / RPP; ++p) {
-                const int row = p * RPP + lane / CPR, ch = lane % CPR;
-                const float4 x = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch);
-                const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
-                float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-                epi8<D, EPI>(a, g, EPI == EPI_PARTIAL ? gz : g, m0 + wm + i * 32 + row, n0 + wn + 8 * ch, val, vecC);
+        for (int i = 0; i < TM; ++i) {
+            if (i > 0) __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * LDC + 32 * j + (lane & 31)] = acc[i][j][v];
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int p = 0; p < 32 / RPP; ++p) {
+                    const int row = p * RPP + lane / CPR, ch = lane % CPR;
+                    const float4 x = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch);
+                    const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
+                    float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+                    epi8<D, EPI>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val,
+                                 vecC);
+                }
             }
         }
+        if (!more) break;
+        t = tn;
+        __syncthreads();   // staging reads are done before the next tile's LDS stores
     }
 }
 
@@ -471,17 +513,21 @@ static bool vec_c_ok(const GemmArgs &a, int epi, int esz)
     return ok;
 }
 
-// Tile size and split-K plan as a function of the problem shape only, so that the
-// workspace can be sized when the context is created.  Splitting k over workgroups
-// costs a second kernel, so it is kept for products with a very long k and few tiles
-// (the backward-data product of a very wide output layer).
+// Tile configuration and split-K plan as a function of the problem shape only, so that
+// the workspace can be sized when the context is created.
+//   tile 128: 128x128 block, 4 waves.  bf16 MFMAs are fast enough that it wins as soon as
+//             it fills the chip once; f32 MFMAs are slow, there smaller blocks spread better.
+//   tile 64 : 64x64 block, 4 waves x kg k-groups; kg > 1 only when there are too few blocks
+//             to give every SIMD a wave.
+//   tile 32 : 64x32 block (2 waves x kg), for the smallest products.
+// Splitting k over workgroups costs a second kernel, so it is kept for products with a very
+// long k and few tiles (the backward-data product of a very wide output layer).
 SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz)
 {
     constexpr int KT = 128;   // split boundaries are multiples of every k-tile size in use
     SplitPlan p{};
+    p.kg = 1;
     const int64_t big_tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * G;
-    // bf16 MFMAs are fast enough that the larger tile wins as soon as it fills the chip once;
-    // f32 MFMAs are slow, there more and smaller workgroups spread the work better
     if (big_tiles >= (esz == 2 ? 256 : 1024) && M > 64 && N > 64) {
         p.tile = 128; p.splits = 1; p.k_per_split = K; p.tiles = big_tiles;
         return p;
@@ -499,14 +545,51 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
     if (kps < KT) kps = KT;
     splits = (K + kps - 1) / kps;
     p.splits = splits; p.k_per_split = kps;
+    const int64_t wgs = p.tiles * splits;
+    if (wgs >= 512 || K < 256) p.kg = 1;             // enough blocks (or too little k to share)
+    else if (wgs <= 192 && N > 32) { p.tile = 32; p.kg = 2; }   // kg: "many", resolved per dtype
+    else p.kg = 2;
     return p;
 }
 
-// Per-dtype tile parameters: k-tile of the large (128x128) and small (64x64) configuration
-// and the number of k-groups of the small one.
+// Per-dtype parameters: k-tile sizes, k-groups of the small configurations.
 template <typename D> struct Cfg;
-template <> struct Cfg<F32> { static constexpr int KG = 4, KT_SMALL = 32, KT_BIG = 32, ST_BIG = 2; };
-template <> struct Cfg<BF16> { static constexpr int KG = 2, KT_SMALL = 32, KT_BIG = 64, ST_BIG = 1; };
+template <> struct Cfg<F32> { static constexpr int KG64 = 4, KG32 = 8, KT_SMALL = 64, KT_BIG = 32, ST_BIG = 2; };
+template <> struct Cfg<BF16> { static constexpr int KG64 = 4, KG32 = 4, KT_SMALL = 64, KT_BIG = 64, ST_BIG = 1; };
+
+// 1-D grid over block tiles.  With many more tiles than the chip holds at once the grid is
+// capped and every workgroup walks several tiles (prefetching across them); otherwise one
+// tile per workgroup.
+template <int BM, int BN, typename K>
+static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, int splits, int kps, hipStream_t st,
+                         bool persist = false)
+{
+    const int tx = (a.N + BN - 1) / BN, ty = (a.M + BM - 1) / BM;
+    const int64_t total = (int64_t)tx * ty * a.G * splits;
+    const int64_t cap = 256 * 3 * 4;   // 256 CUs x 3 resident workgroups x 4
+    const unsigned grid = (unsigned)(persist && total >= 4 * cap ? cap : total);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty);
+}
+
+template <typename D, bool AK, bool BKC, int EPI, bool VEC>
+static void launch_small(const GemmArgs &a, const SplitPlan &p, bool vecC, hipStream_t st)
+{
+    constexpr int KTS = Cfg<D>::KT_SMALL, KG64 = Cfg<D>::KG64, KG32 = Cfg<D>::KG32;
+    if (EPI == EPI_UPDATE) {
+        // k = batch size is short and the block count is large: plain 64x64 blocks, 32-wide k-tiles
+        launch_tiles<64, 64>(k_gemm_mfma<D, AK, BKC, EPI, 64, 64, 2, 2, 1, 3, VEC, 32>, 256, a, vecC, 1, a.K, st, true);
+        return;
+    }
+    if (p.tile == 32)
+        launch_tiles<64, 32>(k_gemm_mfma<D, AK, BKC, EPI, 64, 32, 2, 1, KG32, 3, VEC, KTS>, 128 * KG32, a, vecC,
+                             p.splits, p.k_per_split, st);
+    else if (p.kg > 1)
+        launch_tiles<64, 64>(k_gemm_mfma<D, AK, BKC, EPI, 64, 64, 2, 2, KG64, 3, VEC, KTS>, 256 * KG64, a, vecC,
+                             p.splits, p.k_per_split, st);
+    else
+        launch_tiles<64, 64>(k_gemm_mfma<D, AK, BKC, EPI, 64, 64, 2, 2, 1, 3, VEC, KTS>, 256, a, vecC, p.splits,
+                             p.k_per_split, st);
+}
 
 template <typename D, bool AK, bool BKC, int EPI, bool VEC>
 static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
@@ -515,25 +598,24 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
     const bool vecC = vec_c_ok(a, EPI, esz);
     const bool can_split = EPI != EPI_UPDATE && a.partial != nullptr;
     SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
-    if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes) {
-        p.splits = 1; p.k_per_split = a.K;
-    }
-    constexpr int KG = Cfg<D>::KG, KTS = Cfg<D>::KT_SMALL, KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
+    if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes)
+        p = plan_gemm(a.M, a.N, a.K, a.G, false, esz);
     if (p.tile == 128) {
-        dim3 grid((unsigned)((a.N + 127) / 128), (unsigned)((a.M + 127) / 128), (unsigned)a.G);
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 1, STB, VEC, KTB>), grid, dim3(256), 0, st, a, vecC, 1,
-                           a.K);
+        constexpr int KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
+        // bf16 forward / backward-data: 256x128 blocks (each wave 128x64) halve the LDS traffic
+        // per MFMA; the update product (both operands through transposing reads) stays 128x128
+        if (D::kBytes == 2 && EPI != EPI_UPDATE && a.M > 128)
+            launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI, 256, 128, 2, 2, 1, 1, VEC, 64>, 256, a, vecC, 1, a.K, st);
+        else
+            launch_tiles<128, 128>(k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 2, 2, 1, STB, VEC, KTB>, 256, a, vecC, 1, a.K, st,
+                                   EPI == EPI_UPDATE);
     } else if (p.splits == 1) {
-        dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)a.G);
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI, 64, 64, KG, 3, VEC, KTS>), grid, dim3(256 * KG), 0, st, a, vecC,
-                           1, a.K);
+        launch_small<D, AK, BKC, EPI, VEC>(a, p, vecC, st);
     } else {
         GemmArgs pa = a;
         pa.C = a.partial; pa.ldc = a.N; pa.gC = (int64_t)a.M * a.N;
         const bool vecP = vec_c_ok(pa, EPI_PARTIAL, esz);
-        dim3 grid((unsigned)((a.N + 63) / 64), (unsigned)((a.M + 63) / 64), (unsigned)(a.G * p.splits));
-        hipLaunchKernelGGL((k_gemm_mfma<D, AK, BKC, EPI_PARTIAL, 64, 64, KG, 3, VEC, KTS>), grid, dim3(256 * KG), 0, st,
-                           pa, vecP, p.splits, p.k_per_split);
+        launch_small<D, AK, BKC, EPI_PARTIAL, VEC>(pa, p, vecP, st);
         const int64_t units = (int64_t)a.M * ((a.N + 7) / 8);
         dim3 g2((unsigned)((units + 255) / 256), 1, (unsigned)a.G);
         hipLaunchKernelGGL((k_splitk_finish<D, EPI>), g2, dim3(256), 0, st, a, a.partial, p.splits, vecC);
@@ -577,7 +659,7 @@ static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0 || a.G <= 0) return hipSuccess;
-    if ((a.M + 63) / 64 > 65535 || a.zeros == nullptr) return hipErrorInvalidValue;
+    if (a.zeros == nullptr) return hipErrorInvalidValue;
     return dtype == IST_BF16 ? launch_dtype<BF16>(epi, a, st) : launch_dtype<F32>(epi, a, st);
 }
 

@@ -58,6 +58,9 @@ struct HiddenPlan {          // hidden layer l = 1..t-1
     size_t off_sorted = 0;   // subnet buffer: int32 [N]  neuron id at sorted position P
     size_t off_slot = 0;     // subnet buffer: int32 [N]  sorted position of neuron id
     size_t off_p2q = 0;      // subnet buffer: int32 [N]  sorted position of perm position p
+    size_t off_mask = 0;     // subnet buffer: uint32 [S][words] bit c%32 of word c/32: neuron c is in subnet s
+    size_t off_rank = 0;     // subnet buffer: int32 [S][words]  neurons of subnet s below 32*word
+    int64_t words = 0;       // ceil(N / 32)
     size_t off_invpos = 0;   // workspace:     int32 [N]  perm position of neuron id
 };
 
@@ -97,8 +100,8 @@ enum KernelClass {
 
 // ----------------------------------------------------------------- partition / merge
 hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
-                              int32_t *sorted, int32_t *slot, int32_t *p2q, int32_t *err,
-                              hipStream_t st);
+                              int32_t *sorted, int32_t *slot, int32_t *p2q, uint32_t *mask,
+                              int32_t *rank, int32_t *err, hipStream_t st);
 
 // out[g][i][j] = W[rows ? rows[g*nr+i] : i][cols ? cols[g*nc+j] : j]  (or the
 // reverse copy when scatter is set); transposed: the subnet block is [nc][nr].
@@ -109,6 +112,9 @@ struct CopyArgs {
     const int32_t *rows;     // sorted neuron ids of the row layer, or null
     const int32_t *cols;     // sorted neuron ids of the col layer, or null
     const int32_t *slotc;    // sorted position of each col-layer neuron, or null
+    const uint32_t *maskc;   // per-subnet membership bitmask of the col layer, or null
+    const int32_t *rankc;    // per-subnet prefix counts matching maskc
+    int64_t wordsc;          // words per subnet in maskc / rankc
     int64_t nr, nc;          // rows/cols per subnet block
     int64_t N_out, N_in;     // full sizes
     int32_t G;
@@ -140,7 +146,7 @@ struct GemmArgs {
     float *partial; size_t partial_bytes;     // split-K scratch (fp32 partial products), may be null
     const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
 };
-struct SplitPlan { int tile; int splits; int k_per_split; int64_t tiles; };
+struct SplitPlan { int tile; int splits; int k_per_split; int kg; int64_t tiles; };
 SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz);
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);

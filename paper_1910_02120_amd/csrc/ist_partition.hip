@@ -36,7 +36,8 @@ __global__ void k_perm_check(const int32_t *__restrict__ perm, const int32_t *__
 constexpr int kSortThreads = 1024;
 __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
     const int32_t *__restrict__ invpos, int64_t N, int64_t w, int32_t *__restrict__ sorted,
-    int32_t *__restrict__ slot, int32_t *__restrict__ p2q)
+    int32_t *__restrict__ slot, int32_t *__restrict__ p2q, uint32_t *__restrict__ mask,
+    int32_t *__restrict__ rank, int64_t words)
 {
     __shared__ int32_t wave_cnt[kSortThreads / 64];
     __shared__ int32_t base_sh;
@@ -59,6 +60,15 @@ __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
             total += v;
         }
         int base = base_sh;
+        if (lane == 0) {   // membership bitmask and prefix counts of these 64 neuron ids
+            const int64_t w0 = (c0 + (int64_t)wave * 64) >> 5;
+            const uint32_t lo = (uint32_t)bal, hi = (uint32_t)(bal >> 32);
+            if (w0 < words) { mask[(int64_t)s * words + w0] = lo; rank[(int64_t)s * words + w0] = base + before; }
+            if (w0 + 1 < words) {
+                mask[(int64_t)s * words + w0 + 1] = hi;
+                rank[(int64_t)s * words + w0 + 1] = base + before + __popc(lo);
+            }
+        }
         if (mine) {
             int64_t q = (int64_t)base + before + prefix;
             if (q < w) {   // always true for a valid permutation
@@ -75,14 +85,14 @@ __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
 }
 
 hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
-                              int32_t *sorted, int32_t *slot, int32_t *p2q, int32_t *err,
-                              hipStream_t st)
+                              int32_t *sorted, int32_t *slot, int32_t *p2q, uint32_t *mask,
+                              int32_t *rank, int32_t *err, hipStream_t st)
 {
     const int th = 256;
     const unsigned nb = (unsigned)((N + th - 1) / th);
     hipLaunchKernelGGL(k_perm_invert, dim3(nb), dim3(th), 0, st, perm, N, invpos, err);
     hipLaunchKernelGGL(k_perm_sort, dim3(S), dim3(kSortThreads), 0, st, invpos, N, N / S, sorted,
-                       slot, p2q);
+                       slot, p2q, mask, rank, (N + 31) / 32);
     return hipGetLastError();
 }
 
@@ -162,7 +172,9 @@ __global__ __launch_bounds__(256) void k_rows_transposed(E *__restrict__ W, int6
 // ----------------------------------------------------------------------------
 // column-partitioned blocks (middle and last layers)
 // ----------------------------------------------------------------------------
-// sub[g][i][q] <-> W[rows ? rows[g*nr+i] : i][cols[g*nc+q]]
+// sub[g][i][q] <-> W[rows ? rows[g*nr+i] : i][cols[g*nc+q]].  The column lists are
+// ascending, so consecutive lanes touch ascending addresses of the full row and every
+// line of it is fetched once; four elements per thread are in flight.
 template <typename E, bool SCATTER>
 __global__ __launch_bounds__(256) void k_cols(E *__restrict__ W, int64_t ld, E *__restrict__ sub,
                                               const int32_t *__restrict__ rows,
@@ -175,9 +187,72 @@ __global__ __launch_bounds__(256) void k_cols(E *__restrict__ W, int64_t ld, E *
     E *full = W + r * ld;
     E *pack = sub + ((int64_t)g * nr + i) * nc;
     const int32_t *cg = cols + (int64_t)g * nc;
-    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nc;
-         q += (int64_t)gridDim.x * blockDim.x) {
-        if (SCATTER) full[cg[q]] = pack[q]; else pack[q] = full[cg[q]];
+    constexpr int U = 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q0 < nc; q0 += stride * U) {
+        int32_t c[U];
+        E v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t q = q0 + u * stride;
+            c[u] = q < nc ? cg[q] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t q = q0 + u * stride;
+            if (q < nc) v[u] = SCATTER ? pack[q] : full[c[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t q = q0 + u * stride;
+            if (q < nc) { if (SCATTER) full[c[u]] = v[u]; else pack[q] = v[u]; }
+        }
+    }
+}
+
+// Last layer (every row belongs to all subnets, columns partitioned): one workgroup
+// per row stages the row in LDS, so that the row is read/written along its memory
+// order and every packed block row is written/read as 16-byte pieces; the column
+// permutation happens inside LDS.
+template <typename E, bool SCATTER>
+__global__ __launch_bounds__(256) void k_last_lds(E *__restrict__ W, int64_t ld, E *__restrict__ sub,
+                                                  const int32_t *__restrict__ sorted, int64_t nr,
+                                                  int64_t nc, int32_t G)
+{
+    constexpr int EPC = 16 / sizeof(E);
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    E *row = reinterpret_cast<E *>(lds_raw);
+    const int64_t i = blockIdx.x;
+    uint4 *full = reinterpret_cast<uint4 *>(W + i * ld);
+    const int64_t nchunk = ld / EPC;
+    const int64_t nunit = (int64_t)G * nc / EPC;
+    if (!SCATTER) {
+        for (int64_t c = threadIdx.x; c < nchunk; c += blockDim.x)
+            reinterpret_cast<uint4 *>(row)[c] = full[c];
+        __syncthreads();
+        for (int64_t u = threadIdx.x; u < nunit; u += blockDim.x) {
+            const int64_t P0 = u * EPC;
+            const int64_t g = P0 / nc, q0 = P0 % nc;
+            E e[EPC];
+#pragma unroll
+            for (int j = 0; j < EPC; ++j) e[j] = row[sorted[P0 + j]];
+            uint4 o;
+            __builtin_memcpy(&o, e, 16);
+            *reinterpret_cast<uint4 *>(sub + ((int64_t)g * nr + i) * nc + q0) = o;
+        }
+    } else {
+        for (int64_t u = threadIdx.x; u < nunit; u += blockDim.x) {
+            const int64_t P0 = u * EPC;
+            const int64_t g = P0 / nc, q0 = P0 % nc;
+            uint4 o = *reinterpret_cast<const uint4 *>(sub + ((int64_t)g * nr + i) * nc + q0);
+            E e[EPC];
+            __builtin_memcpy(e, &o, 16);
+#pragma unroll
+            for (int j = 0; j < EPC; ++j) row[sorted[P0 + j]] = e[j];
+        }
+        __syncthreads();
+        for (int64_t c = threadIdx.x; c < nchunk; c += blockDim.x)
+            full[c] = reinterpret_cast<const uint4 *>(row)[c];
     }
 }
 
@@ -203,16 +278,26 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
             hipLaunchKernelGGL((k_rows<E, SCATTER, false>), dim3(nb), dim3(256), 0, st, W, a.ld,
                                sub, a.rows, nrows, a.nc);
     } else {
-        unsigned gx = (unsigned)((a.nc + 255) / 256);
-        if (gx > 64) gx = 64;
+        constexpr int EPC = 16 / sizeof(E);
+        const bool aligned = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (reinterpret_cast<uintptr_t>(sub) % 16 == 0) &&
+                             (a.ld % EPC == 0) && (a.N_in % EPC == 0);
+        // the last layer's columns cover 0..N_in-1 exactly once over the G subnets
+        if (!a.rows && aligned && a.nc % EPC == 0 && a.nc * a.G == a.N_in && a.N_in * sizeof(E) <= 65536 &&
+            a.nr < 0x7fffffffLL) {
+            int th = (int)(a.N_in / EPC);
+            th = th < 64 ? 64 : (th > 256 ? 256 : (th + 63) / 64 * 64);
+            hipLaunchKernelGGL((k_last_lds<E, SCATTER>), dim3((unsigned)a.nr), dim3(th), (size_t)(a.N_in * sizeof(E)), st,
+                               W, a.ld, sub, a.cols, a.nr, a.nc, a.G);
+            return hipGetLastError();
+        }
+        unsigned gx = (unsigned)((a.nc + 1023) / 1024);   // 4 elements per thread
+        if (gx > 8) gx = 8;
         // grid.y is limited to 65535 blocks: split very tall blocks into several launches
         const int64_t max_y = 65535;
         for (int64_t i0 = 0; i0 < a.nr; i0 += max_y) {
             int64_t ny = a.nr - i0 < max_y ? a.nr - i0 : max_y;
-            // rows == nullptr means identity rows: shift the matrix and block pointers instead
             if (a.rows) {
-                // per-group row lists are indexed by g*nr + i: cannot shift, so the kernel
-                // takes nr as the stride and we require nr <= max_y for this case
+                // per-group row lists are indexed by g*nr + i: this path needs nr <= max_y
                 if (a.nr > max_y) return hipErrorInvalidValue;
                 hipLaunchKernelGGL((k_cols<E, SCATTER>), dim3(gx, (unsigned)ny, (unsigned)a.G),
                                    dim3(256), 0, st, W, a.ld, sub, a.rows, a.cols, a.nr, a.nc);
