@@ -168,6 +168,9 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     (void)tables_end;
 
     // ---- workspace ----
+    // Output layers wider than 4096 classes use the two-pass cross-entropy that recomputes the
+    // logits instead of storing them (B x N_t fp32 per subnet would dominate HBM traffic).
+    ctx->fused_out = ctx->dims[t] > 4096;
     size_t w = 0;
     for (int l = 1; l < t; ++l) {
         ctx->hidden[l - 1].off_invpos = w;
@@ -176,8 +179,19 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     for (int l = 1; l <= t; ++l) {
         LayerPlan &L = ctx->layer[l - 1];
         size_t act_e = (l == t) ? sizeof(float) : (size_t)e;
+        if (l == t && ctx->fused_out) act_e = 0;   // logits of a wide output layer are never stored
         L.off_act = w; w = align_up(w + (size_t)S * max_B * L.ldr * act_e);
         L.off_dz = w;  w = align_up(w + (size_t)S * max_B * L.ldr * e);
+    }
+    if (ctx->fused_out) {
+        ctx->nb_max = (int32_t)((ctx->dims[t] + 31) / 32);
+        const size_t rows = (size_t)S * max_B;
+        ctx->off_pmax = w; w = align_up(w + sizeof(float) * rows * ctx->nb_max);
+        ctx->off_psum = w; w = align_up(w + sizeof(float) * rows * ctx->nb_max);
+        ctx->off_qmax = w; w = align_up(w + sizeof(float) * rows * kLseChunksHost);
+        ctx->off_qsum = w; w = align_up(w + sizeof(float) * rows * kLseChunksHost);
+        ctx->off_zlabel = w; w = align_up(w + sizeof(float) * rows);
+        ctx->off_lse = w; w = align_up(w + sizeof(float) * rows);
     }
     ctx->off_zeros = w; w = align_up(w + 256);   // stays zero: source of out-of-range operand chunks
     ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)S * max_B);
@@ -474,10 +488,32 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             a.C = ws + L.off_act; a.ldc = L.ldr; a.gC = (int64_t)B * L.ldr;
             a.M = B; a.N = (int32_t)L.R; a.K = (int32_t)L.C; a.G = S;
             a.bias = bias; a.gBias = L.R;
+            if (l == t && ctx->fused_out) {
+                // pass 1: per-row, per-column-block max / sum(exp); pass 2 (after the row
+                // statistics are combined): recompute the logits and store dz_t directly
+                const int bw = lse_block_width(dt, a.M, a.N, a.K, a.G);
+                a.y = bt->y + row0; a.gY = bt->stride_s;
+                a.pmax = reinterpret_cast<float *>(ws + ctx->off_pmax);
+                a.psum = reinterpret_cast<float *>(ws + ctx->off_psum);
+                a.nb = (int32_t)((L.R + bw - 1) / bw);
+                a.zlabel = reinterpret_cast<float *>(ws + ctx->off_zlabel);
+                a.lse = reinterpret_cast<float *>(ws + ctx->off_lse);
+                a.invB = 1.0f / (float)B;
+                IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_LSE, a, st), "forward gemm (row statistics)");
+                IST_RUN(KC_SOFTMAX_XENT, launch_lse_combine(a.pmax, a.psum, a.nb, reinterpret_cast<float *>(ws + ctx->off_qmax),
+                                                           reinterpret_cast<float *>(ws + ctx->off_qsum), a.zlabel, a.y, a.gY, L.R,
+                                                           reinterpret_cast<float *>(ws + ctx->off_lse), rowloss, S, B, st),
+                        "combine row statistics");
+                a.C = ws + L.off_dz;
+                IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_DZ, a, st), "forward gemm (dz)");
+                continue;
+            }
             IST_RUN(KC_GEMM_FWD, launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
         }
         // ---------------- loss and dz_t ----------------
-        {
+        if (ctx->fused_out) {
+            if (loss_out) IST_RUN(KC_LOSS_REDUCE, launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
+        } else {
             const LayerPlan &L = ctx->layer[t - 1];
             IST_RUN(KC_SOFTMAX_XENT, launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
                                         bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, L.ldr, dt, st),

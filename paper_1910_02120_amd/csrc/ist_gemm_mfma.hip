@@ -197,7 +197,7 @@ template <> struct Row8<uint16_t> {
             uint32_t w[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+                w[i] = f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
             *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
         } else {
 #pragma unroll
@@ -271,6 +271,83 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
         for (int i = 0; i < 8; ++i) val[i] = o[i] - a.lr * val[i];
     }
     Row8<T>::st(static_cast<T *>(a.C) + ci, vec, nv, val);
+}
+
+
+// EPI_LSE: the CPR lanes that hold the 8-column chunks of one row of the wave's column block
+// reduce max and sum(exp) of that block; logits are not stored.  All lanes take part.
+template <typename D, int CPR>
+__device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk, float (&val)[8], bool vecBias,
+                               int label)
+{
+    using T = typename D::T;
+    const bool rowok = m < a.M;
+    const int nv = !rowok ? 0 : (a.N - n0 >= 8 ? 8 : (a.N - n0 > 0 ? a.N - n0 : 0));
+    if (a.bias && nv > 0) {
+        float b[8];
+        Row8<T>::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n0, vecBias && nv == 8, nv, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val[i] += b[i];
+    }
+    // exp(x) = exp2(x * log2(e)): scale once, then only v_exp_f32 per element
+    constexpr float kLog2e = 1.4426950408889634f;
+    float mx = -INFINITY, se = 0.0f;
+    if (nv == 8) {   // the common case, no per-element masks
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, val[i]);
+#pragma unroll
+        for (int o = 1; o < CPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        const float ms = mx * kLog2e;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) se += __builtin_amdgcn_exp2f(fmaf(val[i], kLog2e, -ms));
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mx = i < nv ? fmaxf(mx, val[i]) : mx;
+#pragma unroll
+        for (int o = 1; o < CPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) se += i < nv ? __builtin_amdgcn_exp2f((val[i] - mx) * kLog2e) : 0.0f;
+    }
+#pragma unroll
+    for (int o = 1; o < CPR; o <<= 1) se += __shfl_xor(se, o);
+    if (!rowok) return;
+    if ((threadIdx.x & (CPR - 1)) == 0 && blk < a.nb) {
+        const int64_t pi = ((int64_t)g * a.nb + blk) * a.M + m;   // [g][block][row]: rows are the fast index
+        a.pmax[pi] = mx;
+        a.psum[pi] = se;
+    }
+    if (label >= n0 && label < n0 + nv) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (label == n0 + i) a.zlabel[(int64_t)g * a.M + m] = val[i];
+    }
+}
+
+// EPI_DZ: dz[m][n] = (exp(z - lse_m) - [n == y_m]) / B, stored in the storage dtype.
+template <typename D>
+__device__ inline void epi_dz(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC, int label,
+                              float lse)
+{
+    using T = typename D::T;
+    if (m >= a.M || n0 >= a.N) return;
+    const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
+    const bool vec = vecC && nv == 8;
+    if (a.bias) {
+        float b[8];
+        Row8<T>::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n0, vec, nv, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val[i] += b[i];
+    }
+    constexpr float kLog2e = 1.4426950408889634f;
+    const float ls = lse * kLog2e;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) val[i] = __builtin_amdgcn_exp2f(fmaf(val[i], kLog2e, -ls)) * a.invB;
+    if (label >= n0 && label < n0 + 8) {   // rare: the chunk that holds the label
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (n0 + i == label) val[i] -= a.invB;
+    }
+    Row8<T>::st(static_cast<T *>(a.C) + (int64_t)g * a.gC + (int64_t)m * a.ldc + n0, vec, nv, val);
 }
 
 template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; };
@@ -438,6 +515,20 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
         float *stage = fsm + w4 * (32 * LDC);
         constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
         constexpr int RPP = 64 / CPR;      // rows per pass
+        // per-row inputs of the cross-entropy epilogues, fetched in one batch up front
+        int lab[TM][32 / RPP];
+        float lsv[TM][32 / RPP];
+        if (EPI == EPI_LSE || EPI == EPI_DZ) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int p = 0; p < 32 / RPP; ++p) {
+                    const int m = cm0 + wm + i * 32 + p * RPP + lane / CPR;
+                    const bool ok = m < a.M;
+                    lab[i][p] = ok ? a.y[(int64_t)cg * a.gY + m] : -1;
+                    lsv[i][p] = (EPI == EPI_DZ && ok) ? a.lse[(int64_t)cg * a.M + m] : 0.0f;
+                }
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (i > 0) __syncthreads();
@@ -456,8 +547,14 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
                     const float4 x = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch);
                     const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
                     float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-                    epi8<D, EPI>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val,
-                                 vecC);
+                    if (EPI == EPI_LSE)
+                        epi_lse<D, CPR>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, (cn0 + wn) / (32 * TN), val, vecC,
+                                        lab[i][p]);
+                    else if (EPI == EPI_DZ)
+                        epi_dz<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, lab[i][p], lsv[i][p]);
+                    else
+                        epi8<D, EPI>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
+                                     val, vecC);
                 }
             }
         }
@@ -506,7 +603,9 @@ static bool vec_c_ok(const GemmArgs &a, int epi, int esz)
     const int ch = 16 / out_esz;
     bool ok = reinterpret_cast<uintptr_t>(a.C) % 16 == 0 && a.gC % ch == 0 && a.ldc % ch == 0;
     const int che = 16 / esz;
-    if ((epi == EPI_FWD_RELU || epi == EPI_FWD_LOGITS) && a.bias)
+    if (epi == EPI_LSE)   // nothing is stored: the flag only covers the bias reads
+        return !a.bias || (reinterpret_cast<uintptr_t>(a.bias) % 16 == 0 && a.gBias % (16 / esz) == 0);
+    if ((epi == EPI_FWD_RELU || epi == EPI_FWD_LOGITS || epi == EPI_DZ) && a.bias)
         ok = ok && reinterpret_cast<uintptr_t>(a.bias) % 16 == 0 && a.gBias % che == 0;
     if (epi == EPI_BWD_DATA)
         ok = ok && reinterpret_cast<uintptr_t>(a.mask) % 16 == 0 && a.gMask % che == 0 && a.ldm % che == 0;
@@ -596,7 +695,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
 {
     const int esz = D::kBytes;
     const bool vecC = vec_c_ok(a, EPI, esz);
-    const bool can_split = EPI != EPI_UPDATE && a.partial != nullptr;
+    const bool can_split = EPI != EPI_UPDATE && EPI != EPI_LSE && EPI != EPI_DZ && a.partial != nullptr;
     SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
     if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes)
         p = plan_gemm(a.M, a.N, a.K, a.G, false, esz);
@@ -604,8 +703,13 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
         constexpr int KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
         // bf16 forward / backward-data: 256x128 blocks (each wave 128x64) halve the LDS traffic
         // per MFMA; the update product (both operands through transposing reads) stays 128x128
-        if (D::kBytes == 2 && EPI != EPI_UPDATE && a.M > 128)
-            launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI, 256, 128, 2, 2, 1, 1, VEC, 64>, 256, a, vecC, 1, a.K, st);
+        if (EPI != EPI_UPDATE && a.K <= 256 && p.tiles >= 4 * 3072) {
+            // very short k, very many tiles (wide output layer): walk tiles persistently so that the
+            // loads of the next tile overlap the (arithmetic-heavy) epilogue of the current one
+            launch_tiles<128, 128>(k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 2, 2, 1, STB, VEC, KTB, true>, 256, a, vecC, 1,
+                                   a.K, st, true);
+        } else if (D::kBytes == 2 && EPI != EPI_UPDATE && a.M > 128)
+            launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI, 256, 128, 2, 2, 1, 1, VEC, 64>, 256, a, vecC, 1, a.K, st, EPI == EPI_UPDATE);
         else
             launch_tiles<128, 128>(k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 2, 2, 1, STB, VEC, KTB>, 256, a, vecC, 1, a.K, st,
                                    EPI == EPI_UPDATE);
@@ -645,6 +749,12 @@ static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
     case EPI_FWD_LOGITS:
         if (ak && bk) return launch_cfg<D, true, true, EPI_FWD_LOGITS>(a, st);
         break;
+    case EPI_LSE:
+        if (ak && bk) return launch_cfg<D, true, true, EPI_LSE>(a, st);
+        break;
+    case EPI_DZ:
+        if (ak && bk) return launch_cfg<D, true, true, EPI_DZ>(a, st);
+        break;
     case EPI_BWD_DATA:
         if (ak && !bk) return launch_cfg<D, true, false, EPI_BWD_DATA>(a, st);
         break;
@@ -654,6 +764,12 @@ static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
     default: break;
     }
     return hipErrorInvalidValue;
+}
+
+int lse_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G)
+{
+    const SplitPlan p = plan_gemm(M, N, K, G, false, dtype == IST_BF16 ? 2 : 4);
+    return p.tile == 128 ? 64 : 32;   // 32 * TN of the configuration launch_vec picks
 }
 
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st)

@@ -25,11 +25,14 @@ struct F32 {
 };
 
 __device__ inline float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-__device__ inline uint16_t f32_to_bf16(float f) {  // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+__device__ inline uint16_t f32_to_bf16(float f) {  // round to nearest even (v_cvt_pk_bf16_f32)
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+typedef __bf16 ist_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float ist_f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t f32x2_to_bf16x2(float lo, float hi) {  // lo in bits 0..15
+    ist_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, ist_bf16x2));
 }
 
 struct BF16 {
@@ -74,6 +77,8 @@ struct ist_ctx {
     size_t subnets_bytes = 0, workspace_bytes = 0;
     size_t off_rowloss = 0, off_bitmap = 0, off_err = 0;  // workspace
     size_t off_partial = 0, partial_bytes = 0, off_zeros = 0;
+    bool fused_out = false;   // wide output layer: logits are never stored
+    size_t off_pmax = 0, off_psum = 0, off_qmax = 0, off_qsum = 0, off_zlabel = 0, off_lse = 0; int32_t nb_max = 0;
     char *subnets = nullptr;
     char *workspace = nullptr;
     bool bound = false, partitioned = false;
@@ -132,7 +137,11 @@ hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc,
                          int64_t base_c, bool transposed, int esz, hipStream_t st);
 
 // ----------------------------------------------------------------- training
-enum Epilogue { EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3, EPI_PARTIAL = 4 };
+enum Epilogue {
+    EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3, EPI_PARTIAL = 4,
+    EPI_LSE = 5,   // logits are not stored: per row and column block, max and sum of exp (wide output layers)
+    EPI_DZ = 6     // logits recomputed: store dz = (exp(z - lse) - onehot) / B in the storage dtype
+};
 
 // C[g][m][n] (+)= sum_k A_g(m,k) * B_g(n,k), element (m,k) of A at A + g*gA + m*sam + k*sak.
 struct GemmArgs {
@@ -145,7 +154,19 @@ struct GemmArgs {
     float lr;                                 // EPI_UPDATE: C = C - lr * acc
     float *partial; size_t partial_bytes;     // split-K scratch (fp32 partial products), may be null
     const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
+    // EPI_LSE / EPI_DZ (softmax cross-entropy over a wide output layer, logits never stored)
+    const int32_t *y; int64_t gY;             // labels of the batch rows, per-group stride
+    float *pmax, *psum; int32_t nb;           // [G][M][nb] per column block: max, sum exp(z - max)
+    float *zlabel;                            // [G][M] logit of the label
+    const float *lse;                         // [G][M] log-sum-exp of the row (EPI_DZ)
+    float invB;
 };
+// column-block width (elements) the EPI_LSE epilogue reduces over, for this problem shape
+int lse_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G);
+hipError_t launch_lse_combine(const float *pmax, const float *psum, int32_t nb, float *qmax, float *qsum,
+                              const float *zlabel, const int32_t *y, int64_t gY, int64_t Cn, float *lse,
+                              float *rowloss, int32_t G, int32_t B, hipStream_t st);
+constexpr int kLseChunksHost = 32;   // second-level partials per row (matches the kernels)
 struct SplitPlan { int tile; int splits; int k_per_split; int kg; int64_t tiles; };
 SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz);
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);

@@ -107,6 +107,78 @@ hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out
     return hipGetLastError();
 }
 
+// Row statistics of a wide output layer from the per-column-block partials of the
+// forward pass (layout [g][block][row]): two levels of the usual (max, sum) merge,
+// lse = log sum_blocks psum * exp(pmax - max) + max, loss = lse - z[label].
+constexpr int kLseChunks = 32;
+
+__device__ inline void lse_merge(float &m, float &s, float m2, float s2)
+{
+    const float mx = fmaxf(m, m2);
+    if (mx == -INFINITY) { m = mx; s = 0.0f; return; }
+    s = s * __expf(m - mx) + s2 * __expf(m2 - mx);
+    m = mx;
+}
+
+// level 1: workgroup = 64 rows x 4 waves; wave w takes blocks c0 + w, c0 + w + 4, ... of chunk c
+__global__ __launch_bounds__(256) void k_lse_level1(const float *__restrict__ pmax,
+                                                    const float *__restrict__ psum, int32_t nb, int32_t M,
+                                                    float *__restrict__ qmax, float *__restrict__ qsum)
+{
+    __shared__ float shm[4][64], shs[4][64];
+    const int g = blockIdx.z, c = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 64 + lane;
+    const int per = (nb + kLseChunks - 1) / kLseChunks;
+    const int b0 = c * per, b1 = min(nb, b0 + per);
+    float m = -INFINITY, s = 0.0f;
+    if (row < M) {
+        for (int b = b0 + wave; b < b1; b += 4) {
+            const int64_t i = ((int64_t)g * nb + b) * M + row;
+            lse_merge(m, s, pmax[i], psum[i]);
+        }
+    }
+    shm[wave][lane] = m; shs[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && row < M) {
+        for (int w = 1; w < 4; ++w) lse_merge(m, s, shm[w][lane], shs[w][lane]);
+        const int64_t o = ((int64_t)g * kLseChunks + c) * M + row;
+        qmax[o] = m; qsum[o] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_lse_level2(const float *__restrict__ qmax,
+                                                    const float *__restrict__ qsum, int32_t M,
+                                                    const float *__restrict__ zlabel,
+                                                    const int32_t *__restrict__ y, int64_t gY, int64_t Cn,
+                                                    float *__restrict__ lse, float *__restrict__ rowloss)
+{
+    const int g = blockIdx.y;
+    const int row = blockIdx.x * 256 + threadIdx.x;
+    if (row >= M) return;
+    float m = -INFINITY, s = 0.0f;
+    for (int c = 0; c < kLseChunks; ++c) {
+        const int64_t i = ((int64_t)g * kLseChunks + c) * M + row;
+        lse_merge(m, s, qmax[i], qsum[i]);
+    }
+    const float l = __logf(s) + m;
+    const int64_t r = (int64_t)g * M + row;
+    lse[r] = l;
+    const int32_t label = y[(int64_t)g * gY + row];
+    rowloss[r] = (label >= 0 && label < Cn) ? l - zlabel[r] : 0.0f;
+}
+
+hipError_t launch_lse_combine(const float *pmax, const float *psum, int32_t nb, float *qmax, float *qsum,
+                              const float *zlabel, const int32_t *y, int64_t gY, int64_t Cn, float *lse,
+                              float *rowloss, int32_t G, int32_t B, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_lse_level1, dim3((unsigned)((B + 63) / 64), kLseChunks, (unsigned)G), dim3(256), 0, st, pmax,
+                       psum, nb, B, qmax, qsum);
+    hipLaunchKernelGGL(k_lse_level2, dim3((unsigned)((B + 255) / 256), (unsigned)G), dim3(256), 0, st, qmax, qsum, B,
+                       zlabel, y, gY, Cn, lse, rowloss);
+    return hipGetLastError();
+}
+
 // b_l[g][r] <- b_l[g][r] - lr * sum_b dz_l[g][b][r] for several layers in one launch.
 // A workgroup owns 64 columns of one (layer, subnet); its 4 wavefronts split the
 // batch rows, partial sums meet in LDS, summation order is fixed.

@@ -32,6 +32,7 @@ SHAPES = {
     "cfg4-small": _mk("cfg4-small", "cfg4", dims=(256, 1024, 512, 1024, 100), B=96, k=3, lr=0.05),
     "cfg5-small": _mk("cfg5-small", "cfg5", dims=(3001, 256, 5003), S=8, B=40, k=3, nnz_per_row=20,
                       lr=0.5),
+    "wide-out-f32": _mk("wide-out-f32", "cfg2", dims=(96, 128, 4507), S=2, B=24, k=2, lr=0.5),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
