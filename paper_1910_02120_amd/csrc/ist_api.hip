@@ -96,6 +96,7 @@ CopyArgs copy_args(const ist_ctx *ctx, int l, void *Wfull)
     a.sub = ctx->subnets + L.off_W;
     a.rows = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_sorted) : nullptr;
     a.cols = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_sorted) : nullptr;
+    a.slotr = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_slot) : nullptr;
     a.slotc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_slot) : nullptr;
     a.maskc = L.col_part ? reinterpret_cast<const uint32_t *>(ctx->subnets + ctx->hidden[l - 2].off_mask) : nullptr;
     a.rankc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_rank) : nullptr;

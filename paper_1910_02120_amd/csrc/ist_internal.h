@@ -116,6 +116,7 @@ struct CopyArgs {
     void *sub;               // packed blocks [G][nr][nc] (or [G][nc][nr])
     const int32_t *rows;     // sorted neuron ids of the row layer, or null
     const int32_t *cols;     // sorted neuron ids of the col layer, or null
+    const int32_t *slotr;    // sorted position of each row-layer neuron, or null
     const int32_t *slotc;    // sorted position of each col-layer neuron, or null
     const uint32_t *maskc;   // per-subnet membership bitmask of the col layer, or null
     const int32_t *rankc;    // per-subnet prefix counts matching maskc

@@ -210,6 +210,71 @@ __global__ __launch_bounds__(256) void k_cols(E *__restrict__ W, int64_t ld, E *
     }
 }
 
+// Middle layers (rows and columns both partitioned), LDS-staged: one workgroup per packed
+// row walks the source row in chunks of kMidChunk elements.  A chunk is read (and, for
+// merge, written back) with 16-byte accesses along its memory order; the kept elements of
+// the chunk are the contiguous range [rank(c0), rank(c0 + chunk)) of the packed row (the
+// column list is ascending), so the packed side is read/written contiguously as well and
+// the permutation happens in LDS.  HBM sees whole lines once in each direction.
+constexpr int kMidChunk = 8192;
+template <typename E, bool SCATTER>
+__global__ __launch_bounds__(256) void k_mid_lds(E *__restrict__ W, int64_t ld, E *__restrict__ sub,
+                                                 const int32_t *__restrict__ slotr,
+                                                 const int32_t *__restrict__ cols,
+                                                 const int32_t *__restrict__ rank, int64_t words, int64_t nr,
+                                                 int64_t nc, int64_t N_in, int32_t G)
+{
+    constexpr int EPC = 16 / sizeof(E);
+    constexpr int PER = kMidChunk / EPC / 256;   // 16-byte pieces per thread and chunk
+    __shared__ __attribute__((aligned(16))) E buf[kMidChunk];
+    // workgroups follow the rows of the full matrix, so the rows in flight are neighbours
+    const int64_t P = slotr[blockIdx.x];
+    if (P < 0 || P >= nr * G) return;   // only with tables built from a non-permutation
+    const int g = (int)(P / nr);
+    uint4 *full = reinterpret_cast<uint4 *>(W + (int64_t)blockIdx.x * ld);
+    E *pack = sub + P * nc;
+    const int32_t *cg = cols + (int64_t)g * nc;
+    const int32_t *rg = rank + (int64_t)g * words;
+    const int64_t row_pieces = N_in / EPC;
+    uint4 nxt[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int64_t c = threadIdx.x + 256 * u;
+        nxt[u] = c < row_pieces ? full[c] : uint4{0, 0, 0, 0};
+    }
+    for (int64_t c0 = 0; c0 < N_in; c0 += kMidChunk) {
+        const int64_t cend = c0 + kMidChunk < N_in ? c0 + kMidChunk : N_in;
+        int64_t qlo = rg[c0 >> 5];
+        int64_t qhi = cend < N_in ? rg[cend >> 5] : nc;
+        qlo = qlo < 0 ? 0 : (qlo > nc ? nc : qlo);
+        qhi = qhi < qlo ? qlo : (qhi > nc ? nc : qhi);
+#pragma unroll
+        for (int u = 0; u < PER; ++u) reinterpret_cast<uint4 *>(buf)[threadIdx.x + 256 * u] = nxt[u];
+        __syncthreads();
+        // the next chunk's loads fly while this one is permuted
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int64_t c = (c0 + kMidChunk) / EPC + threadIdx.x + 256 * u;
+            nxt[u] = c < row_pieces ? full[c] : uint4{0, 0, 0, 0};
+        }
+        for (int64_t q = qlo + threadIdx.x; q < qhi; q += 256) {
+            const int64_t off = (int64_t)cg[q] - c0;
+            if (off >= 0 && off < cend - c0) {   // always true for tables built from a permutation
+                if (SCATTER) buf[off] = pack[q]; else pack[q] = buf[off];
+            }
+        }
+        __syncthreads();
+        if (SCATTER) {
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int64_t c = c0 / EPC + threadIdx.x + 256 * u;
+                if (c < row_pieces) full[c] = reinterpret_cast<const uint4 *>(buf)[threadIdx.x + 256 * u];
+            }
+            __syncthreads();
+        }
+    }
+}
+
 // Last layer (every row belongs to all subnets, columns partitioned): one workgroup
 // per row stages the row in LDS, so that the row is read/written along its memory
 // order and every packed block row is written/read as 16-byte pieces; the column
@@ -281,6 +346,13 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
         constexpr int EPC = 16 / sizeof(E);
         const bool aligned = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (reinterpret_cast<uintptr_t>(sub) % 16 == 0) &&
                              (a.ld % EPC == 0) && (a.N_in % EPC == 0);
+        const int64_t all_rows = a.nr * a.G;
+        if (a.slotr && aligned && a.rankc && a.N_in == a.ld && a.N_in % 32 == 0 && all_rows == a.N_out &&
+            all_rows < 0x7fffffffLL) {
+            hipLaunchKernelGGL((k_mid_lds<E, SCATTER>), dim3((unsigned)all_rows), dim3(256), 0, st, W, a.ld, sub, a.slotr,
+                               a.cols, a.rankc, a.wordsc, a.nr, a.nc, a.N_in, a.G);
+            return hipGetLastError();
+        }
         // the last layer's columns cover 0..N_in-1 exactly once over the G subnets
         if (!a.rows && aligned && a.nc % EPC == 0 && a.nc * a.G == a.N_in && a.N_in * sizeof(E) <= 65536 &&
             a.nr < 0x7fffffffLL) {
