@@ -25,6 +25,7 @@
 // The epilogue goes through LDS so that every lane owns 8 consecutive columns of a
 // row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses.
 #include "ist_internal.h"
+#include <cstdlib>
 
 namespace ist {
 
@@ -231,9 +232,32 @@ template <> struct Row8<float> {
     }
 };
 
+// The 8 storage-type values an epilogue combines with its 8 results (the old weights for the
+// update, the activations for the ReLU mask), fetched ahead of time as raw 16-byte pieces.
+template <typename T> struct Pre8 { uint4 v[sizeof(T) / 2]; };
+template <typename T> __device__ inline void pre8_decode(const Pre8<T> &r, float (&o)[8]);
+template <> __device__ inline void pre8_decode<uint16_t>(const Pre8<uint16_t> &r, float (&o)[8])
+{
+    const uint32_t w[4] = {r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[2 * i] = __uint_as_float(w[i] << 16);
+        o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+template <> __device__ inline void pre8_decode<float>(const Pre8<float> &r, float (&o)[8])
+{
+    o[0] = __uint_as_float(r.v[0].x); o[1] = __uint_as_float(r.v[0].y);
+    o[2] = __uint_as_float(r.v[0].z); o[3] = __uint_as_float(r.v[0].w);
+    o[4] = __uint_as_float(r.v[1].x); o[5] = __uint_as_float(r.v[1].y);
+    o[6] = __uint_as_float(r.v[1].z); o[7] = __uint_as_float(r.v[1].w);
+}
+
 // Epilogue for 8 consecutive columns n0..n0+7 of row m (gz: output group index).
+// pre: values fetched ahead for this chunk (used on the 16-byte path only), or null.
 template <typename D, int EPI>
-__device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, float (&val)[8], bool vecC)
+__device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, float (&val)[8], bool vecC,
+                            const Pre8<typename D::T> *pre = nullptr)
 {
     using T = typename D::T;
     if (m >= a.M || n0 >= a.N) return;
@@ -262,11 +286,13 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
     }
     float o[8];
     if (EPI == EPI_BWD_DATA) {
-        Row8<T>::ld(static_cast<const T *>(a.mask) + (int64_t)g * a.gMask + (int64_t)m * a.ldm + n0, vec, nv, o);
+        if (pre && vec) pre8_decode<T>(*pre, o);
+        else Row8<T>::ld(static_cast<const T *>(a.mask) + (int64_t)g * a.gMask + (int64_t)m * a.ldm + n0, vec, nv, o);
 #pragma unroll
         for (int i = 0; i < 8; ++i) val[i] = o[i] > 0.0f ? val[i] : 0.0f;
     } else {   // EPI_UPDATE
-        Row8<T>::ld(static_cast<const T *>(a.C) + ci, vec, nv, o);
+        if (pre && vec) pre8_decode<T>(*pre, o);
+        else Row8<T>::ld(static_cast<const T *>(a.C) + ci, vec, nv, o);
 #pragma unroll
         for (int i = 0; i < 8; ++i) val[i] = o[i] - a.lr * val[i];
     }
@@ -355,14 +381,16 @@ template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; }
 // splits > 1 (EPI_PARTIAL only): the fp32 tile of split sp of group g goes to
 // C + (g*splits + sp) * gC; a second kernel adds the splits in order.
 // WM x WN wavefronts tile the BM x BN block, KG k-groups share it: 64*WM*WN*KG threads.
+// DB: two LDS tile buffers and one barrier per k-tile (ST = 1, KG = 1, not PERSIST): the LDS
+// stores of tile i+1 and the global loads of tile i+2 are issued ahead of the MFMAs of tile i.
 template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
-          bool PERSIST = (EPI == EPI_UPDATE)>
+          bool PERSIST = (EPI == EPI_UPDATE), bool DB = false>
 __global__ __launch_bounds__(64 * WM * WN * KG,
                              // waves per SIMD the register allocator must leave room for: 2 for the
                              // 128x64 wave tile (128 accumulator registers), 3 for the 64x64 one (bf16 kernels)
                              (D::kBytes != 2) ? 1 : ((BM / (32 * WM)) * (BN / (32 * WN)) >= 8) ? 2 : ((KG == 1 && BM >= 128) ? 3 : 1))
-void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
-                                                                 int tiles_x, int tiles_y)
+void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x, int tiles_y, int stagger,
+                 int stagger_sleeps)
 {
     using M = Mma<D, KT>;
     using E = typename M::E;
@@ -372,11 +400,13 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
     using TB = Tile<D, BKC, BN, NT, KT>;
     constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);   // 32x32 MFMA tiles per wave
     constexpr int LDC = 32 * TN + 4;            // staging row pitch (floats)
+    constexpr bool PIPE = DB || (D::kBytes == 2 && KG == 1 && TM * TN == 4);   // fixed MFMA / LDS-read interleave
     constexpr int TILE_BYTES = (TA::ELEMS + TB::ELEMS) * (int)sizeof(E);
     constexpr int RED_BYTES = (KG - 1) * WQ * TM * TN * 16 * 64 * 4;
     constexpr int STAGE_BYTES = WQ * 32 * LDC * 4;
-    constexpr int SMEM = MaxOf<TILE_BYTES, MaxOf<RED_BYTES, STAGE_BYTES>::v>::v;
+    constexpr int SMEM = MaxOf<(DB ? 2 : 1) * TILE_BYTES, MaxOf<RED_BYTES, STAGE_BYTES>::v>::v;
     static_assert(M::KSTEPS % KG == 0, "k-groups must divide the MFMA k-steps of a tile");
+    static_assert(!DB || (ST == 1 && KG == 1), "double-buffered loop: one stage, one k-group");
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
     E *As = reinterpret_cast<E *>(smem);
@@ -410,6 +440,14 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
     };
     decode(t);
 
+    // One resident workgroup per CU walking many tiles: all of them would alternate between the
+    // MFMA-bound main loop and the HBM-bound epilogue in lockstep, leaving each resource idle
+    // half of the time.  Start them in `stagger` phase groups a fraction of a tile apart.
+    if (PERSIST && DB && stagger > 1) {
+        const int phase = (blockIdx.x >> 3) % stagger;   // blockIdx.x & 7 selects the XCD
+        for (int i = 0; i < phase * stagger_sleeps; ++i) __builtin_amdgcn_s_sleep(127);
+    }
+
     f32x16 acc[TM][TN];
     typename TA::Regs ra[ST];
     typename TB::Regs rb[ST];
@@ -420,19 +458,41 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
             TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + s * KT, kend);
         }
     };
-    auto compute = [&]() {
+    // The fragments of MFMA k-step q+1 are read from LDS while the MFMAs of k-step q run.
+    auto compute = [&](const E *Ab, const E *Bb) {
+        constexpr int QN = M::KSTEPS / KG;
+        typename M::Frag fa[2][TM], fb[2][TN];
 #pragma unroll
-        for (int q = 0; q < M::KSTEPS / KG; ++q) {
-            const int ks = q * KG + kg;
-            typename M::Frag fa[TM], fb[TN];
+        for (int i = 0; i < TM; ++i) fa[0][i] = TA::frag(Ab, wm + i * 32, kg, lane);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = TA::frag(As, wm + i * 32, ks, lane);
+        for (int j = 0; j < TN; ++j) fb[0][j] = TB::frag(Bb, wn + j * 32, kg, lane);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = TB::frag(Bs, wn + j * 32, ks, lane);
+        for (int q = 0; q < QN; ++q) {
+            if (q + 1 < QN) {
+                const int ks = (q + 1) * KG + kg;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[(q + 1) & 1][i] = TA::frag(Ab, wm + i * 32, ks, lane);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fb[(q + 1) & 1][j] = TB::frag(Bb, wn + j * 32, ks, lane);
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = M::mma(fa[i], fb[j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = M::mma(fb[q & 1][j], fa[q & 1][i], acc[i][j]);
+        }
+        if (PIPE) {
+            // instruction order for the scheduler: the first k-step's LDS reads, then every MFMA
+            // followed by its share of the next k-step's reads (0x008 = MFMA, 0x100 = LDS read)
+            constexpr int DS_PER = TM * (AK ? 1 : 2) + TN * (BKC ? 1 : 2);
+            constexpr int DPM = (DS_PER + TM * TN - 1) / (TM * TN);
+            __builtin_amdgcn_sched_group_barrier(0x100, DS_PER, 0);
+#pragma unroll
+            for (int q = 0; q < QN; ++q)
+#pragma unroll
+                for (int m = 0; m < TM * TN; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, DPM, 0);
+                }
         }
     };
     prologue();
@@ -446,6 +506,24 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
         const int ntile = (kend - kbeg + KT - 1) / KT;
 
+        if (DB) {
+            constexpr int BUF = TA::ELEMS + TB::ELEMS;
+            TA::store(As, ra[0]);
+            TB::store(Bs, rb[0]);
+            TA::template load<VEC>(ra[0], A, Z, a.sam, a.sak, m0, a.M, kbeg + KT, kend);
+            TB::template load<VEC>(rb[0], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + KT, kend);
+            __syncthreads();
+            for (int it = 0; it < ntile; ++it) {
+                E *cur = As + (it & 1) * BUF, *nxt = As + ((it & 1) ^ 1) * BUF;
+                TA::store(nxt, ra[0]);                 // tile it+1 (zeros past the end of k)
+                TB::store(nxt + TA::ELEMS, rb[0]);
+                TA::template load<VEC>(ra[0], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it + 2) * KT, kend);
+                TB::template load<VEC>(rb[0], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it + 2) * KT, kend);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(cur, cur + TA::ELEMS);
+                __syncthreads();
+            }
+        } else {
         // Main loop: whole groups of ST tiles, no branch around any load (loads past the
         // end of k are masked, not skipped), so the wait counters stay exact.
         int it0 = 0;
@@ -458,7 +536,7 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
                 TA::template load<VEC>(ra[s], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it0 + s + ST) * KT, kend);
                 TB::template load<VEC>(rb[s], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it0 + s + ST) * KT, kend);
                 __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the MFMAs it overlaps with
-                compute();
+                compute(As, Bs);
                 __syncthreads();
             }
         }
@@ -470,11 +548,12 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
                 TA::store(As, ra[s]);
                 TB::store(Bs, rb[s]);
                 __syncthreads();
-                compute();
+                compute(As, Bs);
                 __syncthreads();
             }
         }
 
+        }
         // ---- add the k-groups' accumulators (fixed order kg = 1, 2, ...) ----
         if (KG > 1) {
             if (kg > 0) {
@@ -529,17 +608,50 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
                     lsv[i][p] = (EPI == EPI_DZ && ok) ? a.lse[(int64_t)cg * a.M + m] : 0.0f;
                 }
         }
+        // Old weights (update) / activations (ReLU mask) of the chunks this lane will finish,
+        // PD row slices ahead: the loads are independent of the stores of earlier chunks, which
+        // the compiler cannot know, and would otherwise each wait out a full memory round trip.
+        using T = typename D::T;
+        constexpr bool PRE = (EPI == EPI_UPDATE || EPI == EPI_BWD_DATA);
+        constexpr int NP = 32 / RPP;
+        constexpr int PD = !PRE ? 1 : (DB ? TM : ((D::kBytes == 2 && !PERSIST) ? 2 : 1));
+        Pre8<T> pre[PD][NP];
+        auto preload = [&](int i, Pre8<T> (&dst)[NP]) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                const int m = cm0 + wm + i * 32 + p * RPP + lane / CPR;
+                const int n = cn0 + wn + 8 * (lane % CPR);
+                const bool ok = vecC && kg == 0 && m < a.M && n + 8 <= a.N;
+                const T *src = EPI == EPI_UPDATE
+                                   ? static_cast<const T *>(a.C) + (int64_t)cg * a.gC + (int64_t)m * a.ldc + n
+                                   : static_cast<const T *>(a.mask) + (int64_t)cg * a.gMask + (int64_t)m * a.ldm + n;
+                const uint4 *q = reinterpret_cast<const uint4 *>(ok ? src : reinterpret_cast<const T *>(Z));
+#pragma unroll
+                for (int w = 0; w < (int)(sizeof(T) / 2); ++w) dst[p].v[w] = ok ? q[w] : uint4{0, 0, 0, 0};
+            }
+        };
+        if (PRE) {
+#pragma unroll
+            for (int d = 0; d < PD; ++d)
+                if (d < TM) preload(d, pre[d]);
+        }
+        // The MFMAs take the operands swapped, i.e. they produce the transposed 32x32 blocks:
+        // accumulator v of block (i, j) is row 32 i + lane % 32, column 32 j + 8 (v / 4) +
+        // 4 (lane / 32) + v % 4, so four consecutive registers are four consecutive columns and go
+        // to the staging rows as one 16-byte LDS store.  Each wave stages through its own region:
+        // the LDS executes a wave's accesses in order, no workgroup barrier is needed in here.
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            if (i > 0) __syncthreads();
+            __builtin_amdgcn_wave_barrier();
             if (kg == 0) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * LDC + 32 * j + (lane & 31)] = acc[i][j][v];
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<float4 *>(stage + (lane & 31) * LDC + 32 * j + 8 * q + 4 * (lane >> 5)) =
+                            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
             }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
             if (kg == 0) {
 #pragma unroll
                 for (int p = 0; p < 32 / RPP; ++p) {
@@ -554,9 +666,10 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split,
                         epi_dz<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, lab[i][p], lsv[i][p]);
                     else
                         epi8<D, EPI>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
-                                     val, vecC);
+                                     val, vecC, PRE ? &pre[i % PD][p] : nullptr);
                 }
             }
+            if (PRE && i + PD < TM) preload(i + PD, pre[i % PD]);
         }
         if (!more) break;
         t = tn;
@@ -661,13 +774,13 @@ template <> struct Cfg<BF16> { static constexpr int KG64 = 4, KG32 = 4, KT_SMALL
 // tile per workgroup.
 template <int BM, int BN, typename K>
 static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, int splits, int kps, hipStream_t st,
-                         bool persist = false)
+                         bool persist = false, int64_t cap = 256 * 3 * 4 /* 256 CUs x 3 resident workgroups x 4 */,
+                         int stagger = 0, int stagger_sleeps = 0)
 {
     const int tx = (a.N + BN - 1) / BN, ty = (a.M + BM - 1) / BM;
     const int64_t total = (int64_t)tx * ty * a.G * splits;
-    const int64_t cap = 256 * 3 * 4;   // 256 CUs x 3 resident workgroups x 4
     const unsigned grid = (unsigned)(persist && total >= 4 * cap ? cap : total);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty, stagger, stagger_sleeps);
 }
 
 template <typename D, bool AK, bool BKC, int EPI, bool VEC>
@@ -703,7 +816,37 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
         constexpr int KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
         // bf16 forward / backward-data: 256x128 blocks (each wave 128x64) halve the LDS traffic
         // per MFMA; the update product (both operands through transposing reads) stays 128x128
-        if (EPI != EPI_UPDATE && a.K <= 256 && p.tiles >= 4 * 3072) {
+        bool done = false;
+        if constexpr (D::kBytes == 2 && EPI != EPI_UPDATE) {
+            // 256x256 blocks, 8 waves of 128x64, double-buffered LDS, one workgroup per CU: 128 flop per
+            // byte fetched through the vector memory path, which otherwise saturates before the MFMA pipe
+            if (a.K > 256 && a.M > 128 && a.N >= 256 &&
+                (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 256) {
+                launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, false, true>, 512, a, vecC,
+                                       1, a.K, st, false);
+                done = true;
+            }
+        }
+        if constexpr (D::kBytes == 2 && EPI == EPI_UPDATE) {
+            static const int upd = getenv("IST_UPD") ? atoi(getenv("IST_UPD")) : 1;
+            if (upd == 2 && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 127) / 128) * a.G >= 1024) {
+                launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI, 256, 128, 2, 2, 1, 1, VEC, 64>, 256, a, vecC, 1, a.K, st, true);
+                done = true;
+            } else
+            if (upd == 1 && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
+                launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, false, true>, 512, a, vecC,
+                                       1, a.K, st, false);
+                done = true;
+            } else if (upd >= 3 && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
+                static const int stg = getenv("IST_STG") ? atoi(getenv("IST_STG")) : 4;
+                static const int slp = getenv("IST_SLP") ? atoi(getenv("IST_SLP")) : 1;
+                launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, true, true>, 512, a, vecC,
+                                       1, a.K, st, true, 256, upd == 3 ? 0 : stg, slp);
+                done = true;
+            }
+        }
+        if (done) {
+        } else if (EPI != EPI_UPDATE && a.K <= 256 && p.tiles >= 4 * 3072) {
             // very short k, very many tiles (wide output layer): walk tiles persistently so that the
             // loads of the next tile overlap the (arithmetic-heavy) epilogue of the current one
             launch_tiles<128, 128>(k_gemm_mfma<D, AK, BKC, EPI, 128, 128, 2, 2, 1, STB, VEC, KTB, true>, 256, a, vecC, 1,

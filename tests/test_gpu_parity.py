@@ -33,6 +33,9 @@ SHAPES = {
     "cfg5-small": _mk("cfg5-small", "cfg5", dims=(3001, 256, 5003), S=8, B=40, k=3, nnz_per_row=20,
                       lr=0.5),
     "wide-out-f32": _mk("wide-out-f32", "cfg2", dims=(96, 128, 4507), S=2, B=24, k=2, lr=0.5),
+    # wide enough for the 256x256 block tiles (forward of layer 1, backward-data of layer 2)
+    "big-tiles-bf16": _mk("big-tiles-bf16", "cfg3", dims=(520, 33280, 4352, 10), S=16, B=300, k=2,
+                          lr=0.05),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
