@@ -25,7 +25,6 @@
 // The epilogue goes through LDS so that every lane owns 8 consecutive columns of a
 // row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses.
 #include "ist_internal.h"
-#include <cstdlib>
 
 namespace ist {
 
@@ -828,20 +827,10 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
             }
         }
         if constexpr (D::kBytes == 2 && EPI == EPI_UPDATE) {
-            static const int upd = getenv("IST_UPD") ? atoi(getenv("IST_UPD")) : 1;
-            if (upd == 2 && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 127) / 128) * a.G >= 1024) {
-                launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI, 256, 128, 2, 2, 1, 1, VEC, 64>, 256, a, vecC, 1, a.K, st, true);
-                done = true;
-            } else
-            if (upd == 1 && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
-                launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, false, true>, 512, a, vecC,
-                                       1, a.K, st, false);
-                done = true;
-            } else if (upd >= 3 && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
-                static const int stg = getenv("IST_STG") ? atoi(getenv("IST_STG")) : 4;
-                static const int slp = getenv("IST_SLP") ? atoi(getenv("IST_SLP")) : 1;
+            // wide layers: one persistent 256x256 workgroup per CU, started in 4 phase groups
+            if (a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
                 launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, true, true>, 512, a, vecC,
-                                       1, a.K, st, true, 256, upd == 3 ? 0 : stg, slp);
+                                       1, a.K, st, true, 256, 4, 1);
                 done = true;
             }
         }
