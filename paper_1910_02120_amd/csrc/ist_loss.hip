@@ -206,9 +206,93 @@ __global__ __launch_bounds__(256) void k_bias_update(BiasArgs a)
     }
 }
 
+// Wide layers: a workgroup owns 512 columns (8 per lane, one 16-byte load per lane and row), its
+// 4 wavefronts split the batch rows and keep 4 rows in flight each.  Needs a 16-byte aligned
+// dz with a pitch that is a multiple of 8 elements (bf16) / 4 (f32: two loads per row).
+template <typename D>
+__global__ __launch_bounds__(256) void k_bias_update_wide(BiasJob jb, int32_t B, float lr)
+{
+    using T = typename D::T;
+    constexpr int V = 8;                       // columns per lane
+    constexpr int NV = V * sizeof(T) / 16;     // 16-byte loads per lane and row
+    __shared__ float part[3][64][V + 1];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t c0 = ((int64_t)blockIdx.x * 64 + lane) * V;
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.0f;
+    if (c0 < jb.ld) {   // the padding columns of a row are zero and are not stored below
+        const T *p = static_cast<const T *>(jb.dz) + (int64_t)g * B * jb.ld + c0;
+        auto add = [&](const uint4 (&r)[NV]) {
+            if (sizeof(T) == 2) {
+                const uint32_t w[4] = {r[0].x, r[0].y, r[0].z, r[0].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[2 * i] += __uint_as_float(w[i] << 16);
+                    acc[2 * i + 1] += __uint_as_float(w[i] & 0xffff0000u);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    acc[4 * v] += __uint_as_float(r[v].x); acc[4 * v + 1] += __uint_as_float(r[v].y);
+                    acc[4 * v + 2] += __uint_as_float(r[v].z); acc[4 * v + 3] += __uint_as_float(r[v].w);
+                }
+            }
+        };
+        int b = wave;
+        for (; b + 12 < B; b += 16) {
+            uint4 r[4][NV];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+                    r[u][v] = reinterpret_cast<const uint4 *>(p + (int64_t)(b + 4 * u) * jb.ld)[v];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add(r[u]);
+        }
+        for (; b < B; b += 4) {
+            uint4 r[NV];
+#pragma unroll
+            for (int v = 0; v < NV; ++v) r[v] = reinterpret_cast<const uint4 *>(p + (int64_t)b * jb.ld)[v];
+            add(r);
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) part[wave - 1][lane][i] = acc[i];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float tot = (acc[i] + part[0][lane][i]) + (part[1][lane][i] + part[2][lane][i]);
+            if (c0 + i < jb.R) {
+                T *w = static_cast<T *>(jb.bias) + (int64_t)g * jb.R + c0 + i;
+                *w = D::cvt(D::up(*w) - lr * tot);
+            }
+        }
+    }
+}
+
 hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st)
 {
     if (a.njobs <= 0) return hipSuccess;
+    // wide layers go to the 16-byte kernel, one launch each; the rest share one launch
+    const int che = dtype == IST_BF16 ? 8 : 4;
+    int kept = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        const BiasJob &jb = a.job[j];
+        const bool wide = jb.R >= 2048 && jb.ld % 8 == 0 && reinterpret_cast<uintptr_t>(jb.dz) % 16 == 0 &&
+                          ((int64_t)a.B * jb.ld) % che == 0;
+        if (!wide) { a.job[kept++] = jb; continue; }
+        dim3 grid((unsigned)((jb.ld + 511) / 512), (unsigned)a.G);
+        if (dtype == IST_BF16)
+            hipLaunchKernelGGL(k_bias_update_wide<BF16>, grid, dim3(256), 0, st, jb, a.B, a.lr);
+        else
+            hipLaunchKernelGGL(k_bias_update_wide<F32>, grid, dim3(256), 0, st, jb, a.B, a.lr);
+    }
+    a.njobs = kept;
+    if (a.njobs <= 0) return hipGetLastError();
     int blocks = 0;
     for (int j = 0; j < a.njobs; ++j) {
         a.job[j].blk0 = blocks;
