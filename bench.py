@@ -26,6 +26,11 @@ import ist_inputs as gen
 
 PEAK = {"hbm_GBs": 8000.0, "bf16_TFLOPs": 2500.0, "f32_TFLOPs": 157.3}
 
+# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the 1 GiB copy of
+# --calibrate-copy; the runs and the scale factors are in profiles/.  {workload: {kernel label: bytes}}
+MEASURED_TRAFFIC = {}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -36,6 +41,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run a plain device copy of 1 GiB three times (reference dispatch for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -165,6 +173,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
     cfg = gen.CONFIGS[args.workload]
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     nd = min(cfg.rounds, 4) if cfg.idx <= 3 else 1
     dW, db, perms, data = device_problem(cfg, nd, dev)
     ctx = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B, device="cuda:0")
@@ -202,8 +217,10 @@ def main():
     phase /= reps
     wm = work_model(cfg)
 
-    # ---------------- per-kernel-class pass: same region with events around each launch ----------------
-    roof, classes = None, {}
+    # ---------------- per-kernel pass: the same rounds again, HIP events around every launch ----------------
+    # (events are recorded by the library on the stream it launches on; bracketing every launch
+    # widens the gaps between kernels, so this pass is kept apart from the throughput timing above)
+    roof, classes, kernels = None, {}, []
     if not args.no_profile_pass:
         ctx.profile_enable(True)
         ctx.profile_reset()
@@ -211,26 +228,32 @@ def main():
         for i in range(pr):
             run_round(ctx, cfg, dW, db, perms[i % nd], data[i % nd], None)
         prof = ctx.profile_read()
+        kernels = ctx.profile_kernels()
         ctx.profile_enable(False)
         classes = {kname: dict(ms_per_round=ms / pr, launches_per_round=n / pr) for kname, (ms, n) in prof.items()}
-        dom = max(classes, key=lambda c: classes[c]["ms_per_round"])
-        if dom in wm:
-            bound, work = wm[dom]
-            sec = classes[dom]["ms_per_round"] * 1e-3
-            if bound == "mfma":
-                peak = PEAK["f32_TFLOPs"] if cfg.dtype == "f32" else PEAK["bf16_TFLOPs"]
-                ach = work / sec / 1e12
-                roof = dict(kernel=dom, bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s",
-                            frac=ach / peak, traffic=None,
-                            avg_launch_us=sec * 1e6 / classes[dom]["launches_per_round"])
-            else:
-                ach = work / sec / 1e9
-                roof = dict(kernel=dom, bound="hbm", achieved=ach, peak=PEAK["hbm_GBs"], unit="GB/s",
-                            frac=ach / PEAK["hbm_GBs"], traffic=None,
-                            avg_launch_us=sec * 1e6 / classes[dom]["launches_per_round"])
+        for kr in kernels:
+            kr["ms_per_round"] = kr.pop("ms") / pr
+            kr["avg_launch_us"] = kr["ms_per_round"] * pr * 1e3 / kr["launches"]
+            kr["flops_per_launch"] = kr.pop("flops") / kr["launches"]
+            kr["bytes_per_launch"] = kr.pop("bytes") / kr["launches"]
+            kr["launches_per_round"] = kr.pop("launches") / pr
+        kernels.sort(key=lambda kr: -kr["ms_per_round"])
+        dom = kernels[0]
+        sec = dom["avg_launch_us"] * 1e-6
+        traffic = MEASURED_TRAFFIC.get(args.workload, {}).get(dom["label"])
+        if dom["flops_per_launch"] > 0:
+            peak = PEAK["f32_TFLOPs"] if cfg.dtype == "f32" else PEAK["bf16_TFLOPs"]
+            ach = dom["flops_per_launch"] / sec / 1e12
+            roof = dict(kernel=dom["label"], bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
+                        traffic=traffic, avg_launch_us=dom["avg_launch_us"], flops_per_launch=dom["flops_per_launch"])
+        elif dom["bytes_per_launch"] > 0:
+            ach = dom["bytes_per_launch"] / sec / 1e9
+            roof = dict(kernel=dom["label"], bound="hbm", achieved=ach, peak=PEAK["hbm_GBs"], unit="GB/s",
+                        frac=ach / PEAK["hbm_GBs"], traffic=traffic, avg_launch_us=dom["avg_launch_us"],
+                        bytes_per_launch=dom["bytes_per_launch"])
         else:
-            roof = dict(kernel=dom, bound="hbm", achieved=None, peak=PEAK["hbm_GBs"], unit="GB/s",
-                        frac=None, traffic=None)
+            roof = dict(kernel=dom["label"], bound="hbm", achieved=None, peak=PEAK["hbm_GBs"], unit="GB/s",
+                        frac=None, traffic=traffic, avg_launch_us=dom["avg_launch_us"])
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -255,6 +278,7 @@ def main():
             "merge_GBs_useful": wm["useful_copy_bytes"] / (phase[2] * 1e-3) / 1e9,
         },
         "kernel_classes": classes,
+        "kernels": kernels[:8],
         "roofline": roof,
         "cpu_baseline": cpu,
         "loss_first_round": [float(first_loss[:, 0].mean()), float(first_loss[:, -1].mean())],

@@ -158,6 +158,22 @@ ist_status ist_profile_read(ist_ctx *ctx, int32_t kernel_class, double *total_ms
 int32_t ist_profile_classes(void);
 const char *ist_profile_class_name(int32_t kernel_class);
 
+/*
+ * The same records grouped by kernel: one entry per distinct kernel label (kernel
+ * and launch configuration, e.g. "gemm_fwd_relu_bf16_256x256_t512").
+ * ist_profile_kernel_count returns the number of entries since the last reset;
+ * ist_profile_kernel copies entry `index`: its label (NUL-terminated, truncated to
+ * label_cap), its kernel class, the summed kernel time [ms], the number of launches,
+ * and the algorithmic work summed over those launches: flops (2*M*N*K per product
+ * and subnet; 0 for copy kernels) and bytes (copy kernels: the cache-line-granular
+ * minimum - rows a block touches are read whole, and rewritten whole on merge when
+ * their columns are partitioned; 0 where not tracked).  All pointers [host].
+ */
+ist_status ist_profile_kernel_count(ist_ctx *ctx, int32_t *count);
+ist_status ist_profile_kernel(ist_ctx *ctx, int32_t index, char *label, size_t label_cap,
+                              int32_t *kernel_class, double *total_ms, int64_t *launches,
+                              double *flops, double *bytes);
+
 const char *ist_last_error(const ist_ctx *ctx);
 const char *ist_version(void);
 

@@ -24,7 +24,8 @@ IST_DENSE, IST_CSR = 0, 1
 EXPORTS = ["ist_create", "ist_destroy", "ist_subnets_bytes", "ist_workspace_bytes", "ist_bind",
            "ist_set_checked", "ist_partition", "ist_subnet_steps", "ist_merge", "ist_subnet_export",
            "ist_subnet_shape", "ist_last_error", "ist_version", "ist_profile_enable",
-           "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name"]
+           "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name",
+           "ist_profile_kernel_count", "ist_profile_kernel"]
 
 
 class ISTError(RuntimeError):
@@ -75,6 +76,10 @@ def load_library() -> C.CDLL:
     lib.ist_profile_enable.argtypes = [p, C.c_int32]
     lib.ist_profile_reset.argtypes = [p]
     lib.ist_profile_read.argtypes = [p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.ist_profile_kernel_count.argtypes = [p, C.POINTER(C.c_int32)]
+    lib.ist_profile_kernel.argtypes = [p, C.c_int32, C.c_char_p, C.c_size_t, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                       C.POINTER(C.c_double)]
     lib.ist_profile_classes.argtypes = []
     lib.ist_profile_class_name.argtypes = [C.c_int32]
     for name in EXPORTS:
@@ -240,6 +245,20 @@ class ISTContext:
             self._check(self.lib.ist_profile_read(self._ctx, c, C.byref(ms), C.byref(n)))
             if n.value:
                 out[self.lib.ist_profile_class_name(c).decode()] = (ms.value, n.value)
+        return out
+
+    def profile_kernels(self):
+        """[{label, kernel_class, ms, launches, flops, bytes}] per kernel label since the last reset."""
+        n = C.c_int32()
+        self._check(self.lib.ist_profile_kernel_count(self._ctx, C.byref(n)))
+        out = []
+        buf = C.create_string_buffer(96)
+        for i in range(n.value):
+            cls, ms, cnt, fl, by = C.c_int32(), C.c_double(), C.c_int64(), C.c_double(), C.c_double()
+            self._check(self.lib.ist_profile_kernel(self._ctx, i, buf, len(buf), C.byref(cls), C.byref(ms),
+                                                    C.byref(cnt), C.byref(fl), C.byref(by)))
+            out.append(dict(label=buf.value.decode(), kernel_class=self.lib.ist_profile_class_name(cls.value).decode(),
+                            ms=ms.value, launches=cnt.value, flops=fl.value, bytes=by.value))
         return out
 
     def close(self):

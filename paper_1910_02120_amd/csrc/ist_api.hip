@@ -34,6 +34,17 @@ ist_status hip_fail(ist_ctx *ctx, hipError_t e, const char *where)
         if (e_ != hipSuccess) return hip_fail(ctx, e_, where); \
     } while (0)
 
+}  // namespace
+namespace ist {
+thread_local KernelTag g_tag = {};
+void tag_kernel(const char *label, double flops, double bytes)
+{
+    snprintf(g_tag.kernel, sizeof(g_tag.kernel), "%s", label);
+    g_tag.flops = flops; g_tag.bytes = bytes;
+}
+}  // namespace ist
+namespace {
+
 const char *kClassNames[KC_COUNT] = {
     "perm_tables", "partition_copy", "merge_copy", "bias_copy", "gemm_forward", "gemm_backward_data",
     "gemm_update", "softmax_xent", "loss_reduce", "bias_update", "csr_forward", "csr_update"};
@@ -53,8 +64,10 @@ hipEvent_t prof_event(ist_ctx *ctx)
 void prof_begin(ist_ctx *ctx, int cls, hipStream_t st)
 {
     if (!ctx->prof_on) return;
-    ist_ctx::ProfRec r{cls, prof_event(ctx), prof_event(ctx)};
+    ist_ctx::ProfRec r{};
+    r.cls = cls; r.start = prof_event(ctx); r.stop = prof_event(ctx);
     if (!r.start || !r.stop) return;
+    g_tag.kernel[0] = 0; g_tag.flops = 0.0; g_tag.bytes = 0.0;
     (void)hipEventRecord(r.start, st);
     ctx->prof_recs.push_back(r);
 }
@@ -62,7 +75,10 @@ void prof_begin(ist_ctx *ctx, int cls, hipStream_t st)
 void prof_end(ist_ctx *ctx, hipStream_t st)
 {
     if (!ctx->prof_on || ctx->prof_recs.empty()) return;
-    (void)hipEventRecord(ctx->prof_recs.back().stop, st);
+    ist_ctx::ProfRec &r = ctx->prof_recs.back();
+    (void)hipEventRecord(r.stop, st);
+    snprintf(r.kernel, sizeof(r.kernel), "%s", g_tag.kernel[0] ? g_tag.kernel : kClassNames[r.cls]);
+    r.flops = g_tag.flops; r.bytes = g_tag.bytes;
 }
 
 // launch one kernel class, bracketed by events when profiling is on
@@ -265,6 +281,48 @@ ist_status ist_profile_read(ist_ctx *ctx, int32_t cls, double *total_ms, int64_t
     }
     *total_ms = tot;
     *launches = n;
+    return IST_OK;
+}
+
+// Per-kernel view of the same records: launches grouped by kernel label.
+namespace {
+struct KernelAgg { std::string label; int cls; double ms, flops, bytes; int64_t n; };
+ist_status aggregate(ist_ctx *ctx, std::vector<KernelAgg> &out)
+{
+    if (!ctx->prof_recs.empty()) IST_HIP(hipEventSynchronize(ctx->prof_recs.back().stop), "profile read");
+    for (auto &r : ctx->prof_recs) {
+        float ms = 0.0f;
+        IST_HIP(hipEventElapsedTime(&ms, r.start, r.stop), "profile read");
+        KernelAgg *k = nullptr;
+        for (auto &a : out) if (a.cls == r.cls && a.label == r.kernel) { k = &a; break; }
+        if (!k) { out.push_back(KernelAgg{r.kernel, r.cls, 0.0, 0.0, 0.0, 0}); k = &out.back(); }
+        k->ms += ms; k->flops += r.flops; k->bytes += r.bytes; ++k->n;
+    }
+    return IST_OK;
+}
+}  // namespace
+
+ist_status ist_profile_kernel_count(ist_ctx *ctx, int32_t *count)
+{
+    if (!ctx || !count) return IST_EINVAL;
+    std::vector<KernelAgg> agg;
+    const ist_status s = aggregate(ctx, agg);
+    if (s != IST_OK) return s;
+    *count = (int32_t)agg.size();
+    return IST_OK;
+}
+
+ist_status ist_profile_kernel(ist_ctx *ctx, int32_t index, char *label, size_t label_cap, int32_t *kernel_class,
+                              double *total_ms, int64_t *launches, double *flops, double *bytes)
+{
+    if (!ctx || !label || label_cap == 0 || !kernel_class || !total_ms || !launches || !flops || !bytes) return IST_EINVAL;
+    std::vector<KernelAgg> agg;
+    const ist_status s = aggregate(ctx, agg);
+    if (s != IST_OK) return s;
+    if (index < 0 || index >= (int32_t)agg.size()) return IST_EINVAL;
+    const KernelAgg &k = agg[index];
+    snprintf(label, label_cap, "%s", k.label.c_str());
+    *kernel_class = k.cls; *total_ms = k.ms; *launches = k.n; *flops = k.flops; *bytes = k.bytes;
     return IST_OK;
 }
 

@@ -26,6 +26,8 @@
 // row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses.
 #include "ist_internal.h"
 
+#include <cstdio>
+
 namespace ist {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -751,6 +753,12 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
         const int64_t most = K / (16 * KT);           // at least 16 k-tiles per split
         splits = (int)(want < most ? want : most);
         if (splits < 1) splits = 1;
+    } else if (allow_split && p.tiles <= 32 && K >= 512) {
+        // a handful of blocks walking a long k (narrow output layer): latency-bound, spread k over the chip
+        const int64_t want = 512 / p.tiles;
+        const int64_t most = K / KT;
+        splits = (int)(want < most ? want : most);
+        if (splits < 1) splits = 1;
     }
     int kps = ((K + splits - 1) / splits + KT - 1) / KT * KT;
     if (kps < KT) kps = KT;
@@ -771,6 +779,8 @@ template <> struct Cfg<BF16> { static constexpr int KG64 = 4, KG32 = 4, KT_SMALL
 // 1-D grid over block tiles.  With many more tiles than the chip holds at once the grid is
 // capped and every workgroup walks several tiles (prefetching across them); otherwise one
 // tile per workgroup.
+static thread_local const char *s_label = "";   // product and storage type of the launch in progress
+
 template <int BM, int BN, typename K>
 static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, int splits, int kps, hipStream_t st,
                          bool persist = false, int64_t cap = 256 * 3 * 4 /* 256 CUs x 3 resident workgroups x 4 */,
@@ -779,6 +789,10 @@ static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, in
     const int tx = (a.N + BN - 1) / BN, ty = (a.M + BM - 1) / BM;
     const int64_t total = (int64_t)tx * ty * a.G * splits;
     const unsigned grid = (unsigned)(persist && total >= 4 * cap ? cap : total);
+    char label[64];
+    snprintf(label, sizeof(label), "gemm_%s_%dx%d_t%d%s%s", s_label, BM, BN, threads, persist ? "_persistent" : "",
+             splits > 1 ? "_splitk" : "");
+    tag_kernel(label, 2.0 * a.M * a.N * (double)a.K * a.G, 0.0);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty, stagger, stagger_sleeps);
 }
 
@@ -807,6 +821,10 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
 {
     const int esz = D::kBytes;
     const bool vecC = vec_c_ok(a, EPI, esz);
+    static const char *const kEpi[] = {"fwd_relu", "fwd_logits", "bwd_data", "update", "partial", "fwd_lse", "fwd_dz"};
+    static thread_local char lab[40];
+    snprintf(lab, sizeof(lab), "%s_%s%s", kEpi[EPI], esz == 2 ? "bf16" : "f32", VEC ? "" : "_novec");
+    s_label = lab;
     const bool can_split = EPI != EPI_UPDATE && EPI != EPI_LSE && EPI != EPI_DZ && a.partial != nullptr;
     SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
     if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes)

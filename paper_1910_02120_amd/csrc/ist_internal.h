@@ -85,8 +85,8 @@ struct ist_ctx {
     int32_t checked = 0;
     std::string err;
 
-    // optional per-kernel-class timing (HIP events around every launch)
-    struct ProfRec { int cls; hipEvent_t start, stop; };
+    // optional per-launch timing (HIP events around every launch)
+    struct ProfRec { int cls; hipEvent_t start, stop; char kernel[64]; double flops, bytes; };
     bool prof_on = false;
     std::vector<ProfRec> prof_recs;
     std::vector<hipEvent_t> prof_free;
@@ -102,6 +102,12 @@ enum KernelClass {
     KC_GEMM_UPDATE, KC_SOFTMAX_XENT, KC_LOSS_REDUCE, KC_BIAS_UPDATE, KC_CSR_FORWARD, KC_CSR_UPDATE,
     KC_COUNT
 };
+
+// What the last launcher call ran: kernel label (launch configuration), algorithmic flops and
+// bytes of that launch.  Written by the launchers, read by the profiling hooks of the API.
+struct KernelTag { char kernel[64]; double flops, bytes; };
+extern thread_local KernelTag g_tag;
+void tag_kernel(const char *label, double flops, double bytes);
 
 // ----------------------------------------------------------------- partition / merge
 hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,

@@ -326,7 +326,15 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
 {
     E *W = static_cast<E *>(a.W);
     E *sub = static_cast<E *>(a.sub);
+    // bytes any kernel has to move at cache-line granularity: the rows a block touches are read
+    // whole, and rewritten whole on merge when their columns are partitioned
+    const double esz = sizeof(E);
+    const double sub_b = (double)a.G * a.nr * a.nc * esz;
+    const double rows_b = (a.rows ? (double)a.G * a.nr : (double)a.N_out) * a.N_in * esz;
+    const double line_b = !a.cols ? 2.0 * sub_b
+                                  : (SCATTER && a.rows ? 2.0 * rows_b + sub_b : rows_b + sub_b);
     if (a.transposed) {
+        tag_kernel(SCATTER ? "k_rows_transposed<scatter>" : "k_rows_transposed<gather>", 0.0, line_b);
         dim3 grid((unsigned)((a.nc + 63) / 64), (unsigned)((a.nr + 63) / 64), (unsigned)a.G);
         hipLaunchKernelGGL((k_rows_transposed<E, SCATTER>), grid, dim3(256), 0, st, W, a.ld, sub,
                            a.rows, a.nr, a.nc);
@@ -336,6 +344,7 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
                          (reinterpret_cast<uintptr_t>(W) % 16 == 0) &&
                          (reinterpret_cast<uintptr_t>(sub) % 16 == 0);
         unsigned nb = (unsigned)(nrows < 65536 ? nrows : 65536);
+        tag_kernel(SCATTER ? "k_rows<scatter>" : "k_rows<gather>", 0.0, line_b);
         if (vec)
             hipLaunchKernelGGL((k_rows<E, SCATTER, true>), dim3(nb), dim3(256), 0, st, W, a.ld, sub,
                                a.rows, nrows, a.nc);
@@ -349,6 +358,7 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
         const int64_t all_rows = a.nr * a.G;
         if (a.slotr && aligned && a.rankc && a.N_in == a.ld && a.N_in % 32 == 0 && all_rows == a.N_out &&
             all_rows < 0x7fffffffLL) {
+            tag_kernel(SCATTER ? "k_mid_lds<scatter>" : "k_mid_lds<gather>", 0.0, line_b);
             hipLaunchKernelGGL((k_mid_lds<E, SCATTER>), dim3((unsigned)all_rows), dim3(256), 0, st, W, a.ld, sub, a.slotr,
                                a.cols, a.rankc, a.wordsc, a.nr, a.nc, a.N_in, a.G);
             return hipGetLastError();
@@ -358,10 +368,12 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
             a.nr < 0x7fffffffLL) {
             int th = (int)(a.N_in / EPC);
             th = th < 64 ? 64 : (th > 256 ? 256 : (th + 63) / 64 * 64);
+            tag_kernel(SCATTER ? "k_last_lds<scatter>" : "k_last_lds<gather>", 0.0, line_b);
             hipLaunchKernelGGL((k_last_lds<E, SCATTER>), dim3((unsigned)a.nr), dim3(th), (size_t)(a.N_in * sizeof(E)), st,
                                W, a.ld, sub, a.cols, a.nr, a.nc, a.G);
             return hipGetLastError();
         }
+        tag_kernel(SCATTER ? "k_cols<scatter>" : "k_cols<gather>", 0.0, line_b);
         unsigned gx = (unsigned)((a.nc + 1023) / 1024);   // 4 elements per thread
         if (gx > 8) gx = 8;
         // grid.y is limited to 65535 blocks: split very tall blocks into several launches
