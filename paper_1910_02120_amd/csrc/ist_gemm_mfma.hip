@@ -753,7 +753,7 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
         const int64_t most = K / (16 * KT);           // at least 16 k-tiles per split
         splits = (int)(want < most ? want : most);
         if (splits < 1) splits = 1;
-    } else if (allow_split && p.tiles <= 32 && K >= 512) {
+    } else if (allow_split && (p.tiles <= 32 ? K >= 512 : (p.tiles <= 128 && K >= 4096))) {
         // a handful of blocks walking a long k (narrow output layer): latency-bound, spread k over the chip
         const int64_t want = 512 / p.tiles;
         const int64_t most = K / KT;
