@@ -407,7 +407,6 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
     constexpr int STAGE_BYTES = WQ * 32 * LDC * 4;
     constexpr int SMEM = MaxOf<(DB ? 2 : 1) * TILE_BYTES, MaxOf<RED_BYTES, STAGE_BYTES>::v>::v;
     static_assert(M::KSTEPS % KG == 0, "k-groups must divide the MFMA k-steps of a tile");
-    static_assert(!DB || (ST == 1 && KG == 1), "double-buffered loop: one stage, one k-group");
 
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
     E *As = reinterpret_cast<E *>(smem);
@@ -508,22 +507,34 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
         const int ntile = (kend - kbeg + KT - 1) / KT;
 
         if (DB) {
+            // k-tile j waits in registers ra[j % ST] until it is stored to LDS buffer j % 2, one
+            // iteration before it is used; U iterations make one period of both indices.
             constexpr int BUF = TA::ELEMS + TB::ELEMS;
+            constexpr int U = (ST % 2 == 0) ? ST : 2 * ST;
             TA::store(As, ra[0]);
             TB::store(Bs, rb[0]);
-            TA::template load<VEC>(ra[0], A, Z, a.sam, a.sak, m0, a.M, kbeg + KT, kend);
-            TB::template load<VEC>(rb[0], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + KT, kend);
+            TA::template load<VEC>(ra[0], A, Z, a.sam, a.sak, m0, a.M, kbeg + ST * KT, kend);
+            TB::template load<VEC>(rb[0], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + ST * KT, kend);
             __syncthreads();
-            for (int it = 0; it < ntile; ++it) {
-                E *cur = As + (it & 1) * BUF, *nxt = As + ((it & 1) ^ 1) * BUF;
-                TA::store(nxt, ra[0]);                 // tile it+1 (zeros past the end of k)
-                TB::store(nxt + TA::ELEMS, rb[0]);
-                TA::template load<VEC>(ra[0], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it + 2) * KT, kend);
-                TB::template load<VEC>(rb[0], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it + 2) * KT, kend);
+            auto step = [&](int it, int u) {
+                E *cur = As + (u & 1) * BUF, *nxt = As + ((u & 1) ^ 1) * BUF;
+                const int sg = (u + 1) % ST;
+                TA::store(nxt, ra[sg]);                 // tile it+1 (zeros past the end of k)
+                TB::store(nxt + TA::ELEMS, rb[sg]);
+                TA::template load<VEC>(ra[sg], A, Z, a.sam, a.sak, m0, a.M, kbeg + (it + 1 + ST) * KT, kend);
+                TB::template load<VEC>(rb[sg], B, Z, a.sbn, a.sbk, n0, a.N, kbeg + (it + 1 + ST) * KT, kend);
                 __builtin_amdgcn_sched_barrier(0);
                 compute(cur, cur + TA::ELEMS);
                 __syncthreads();
+            };
+            int it0 = 0;
+            for (; it0 + U <= ntile; it0 += U) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) step(it0 + u, u);
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (it0 + u < ntile) step(it0 + u, u);
         } else {
         // Main loop: whole groups of ST tiles, no branch around any load (loads past the
         // end of k are masked, not skipped), so the wait counters stay exact.
@@ -805,8 +816,8 @@ static void launch_small(const GemmArgs &a, const SplitPlan &p, bool vecC, hipSt
         launch_tiles<64, 64>(k_gemm_mfma<D, AK, BKC, EPI, 64, 64, 2, 2, 1, 3, VEC, 32>, 256, a, vecC, 1, a.K, st, true);
         return;
     }
-    if (p.tile == 32)
-        launch_tiles<64, 32>(k_gemm_mfma<D, AK, BKC, EPI, 64, 32, 2, 1, KG32, 3, VEC, KTS>, 128 * KG32, a, vecC,
+    if (p.tile == 32)   // double-buffered: one barrier per k-tile for the 8..16 waves of these workgroups
+        launch_tiles<64, 32>(k_gemm_mfma<D, AK, BKC, EPI, 64, 32, 2, 1, KG32, 1, VEC, KTS, false, true>, 128 * KG32, a, vecC,
                              p.splits, p.k_per_split, st);
     else if (p.kg > 1)
         launch_tiles<64, 64>(k_gemm_mfma<D, AK, BKC, EPI, 64, 64, 2, 2, KG64, 3, VEC, KTS>, 256 * KG64, a, vecC,
