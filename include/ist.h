@@ -82,7 +82,7 @@ typedef struct {
 typedef struct ist_ctx ist_ctx;
 
 /* Creates the host-side plan for one network shape.  No device work.
- * IST_ESHAPE if S does not divide a hidden width or max_B < 1. */
+ * IST_ESHAPE if S does not divide a hidden width or max_B < 1; IST_EUNSUPPORTED if S > 4096. */
 ist_status ist_create(const ist_model_desc *desc, int32_t max_B, ist_ctx **out);
 ist_status ist_destroy(ist_ctx *ctx);
 
@@ -130,8 +130,9 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *batch, float lr, int3
  * ist_merge - Section 2.1 "Training Subnets": subnet parameters are copied back
  * into the full network; blocks are disjoint so nothing collides, and entries
  * of W owned by no subnet keep their bits.  Hidden biases return to their
- * neuron; b_t becomes the mean over subnets (binary32 sum in subnet order times
- * 1/S, rounded to dtype).  Writes `params` in place; subnets stay valid.
+ * neuron; b_t becomes the mean over subnets (binary32 sum as a balanced pairwise
+ * tree over the subnet index, times 1/S, rounded to dtype: exact for identical
+ * copies when S is a power of two).  Writes `params` in place; subnets stay valid.
  */
 ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream);
 

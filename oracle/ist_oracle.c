@@ -106,17 +106,23 @@ void ist_oracle_scatter(uint8_t *W, int64_t ncols_full, int64_t esz,
 }
 
 /* Output bias after merge: every subnet holds a copy of the shared output
-   neurons' bias; the merged value is their mean, summed in binary32 in subnet
-   order and multiplied by 1/S in binary32, then rounded to the storage type. */
+   neurons' bias; the merged value is their mean.  The S values are added in
+   binary32 as a balanced pairwise tree over the subnet index (neighbours first,
+   then pairs of pairs, ...), multiplied by 1/S in binary32 and rounded to the
+   storage type.  With S a power of two and S identical copies every addition
+   and the scaling are exact, so merge(partition(b)) == b bit for bit. */
 void ist_oracle_merge_out_bias(const double *bsub /* [S][n] */, int32_t S, int64_t n,
                                int32_t mode, double *out)
 {
     float inv = 1.0f / (float)S;
+    float *v = (float *)malloc((size_t)S * sizeof(float));
     for (int64_t i = 0; i < n; ++i) {
-        float acc = 0.0f;
-        for (int32_t s = 0; s < S; ++s) acc += (float)bsub[(int64_t)s * n + i];
-        out[i] = round_store((double)(acc * inv), mode == 0 ? 1 : mode);
+        for (int32_t s = 0; s < S; ++s) v[s] = (float)bsub[(int64_t)s * n + i];
+        for (int32_t d = 1; d < S; d *= 2)
+            for (int32_t s = 0; s + d < S; s += 2 * d) v[s] = v[s] + v[s + d];
+        out[i] = round_store((double)(v[0] * inv), mode == 0 ? 1 : mode);
     }
+    free(v);
 }
 
 /* ------------------------------------------------------ local SGD on a subnet */

@@ -143,6 +143,7 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         (d->input != IST_DENSE && d->input != IST_CSR) || (d->has_bias != 0 && d->has_bias != 1))
         return IST_EINVAL;
     if (max_B < 1) return IST_ESHAPE;
+    if (d->S > 4096) return IST_EUNSUPPORTED;   // the output-bias mean is a two-level tree of 64
     for (int l = 0; l <= d->t; ++l) {
         if (d->dims[l] < 1 || d->dims[l] > 0x7fffffffLL) return IST_ESHAPE;
         if (l > 0 && l < d->t && d->dims[l] % d->S != 0) return IST_ESHAPE;

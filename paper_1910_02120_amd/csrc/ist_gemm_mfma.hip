@@ -900,27 +900,27 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t st)
 template <typename D>
 static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
 {
-    const bool ak = a.sak == 1, bk = a.sbk == 1;
-    if (!ak && a.sam != 1) return hipErrorInvalidValue;
-    if (!bk && a.sbn != 1) return hipErrorInvalidValue;
+    // which index of an operand is contiguous follows from the product (with a 1-wide operand both
+    // strides are 1 and either reading is right)
+    const bool a_k = a.sak == 1, a_m = a.sam == 1, b_k = a.sbk == 1, b_n = a.sbn == 1;
     switch (epi) {
     case EPI_FWD_RELU:
-        if (ak && bk) return launch_cfg<D, true, true, EPI_FWD_RELU>(a, st);
+        if (a_k && b_k) return launch_cfg<D, true, true, EPI_FWD_RELU>(a, st);
         break;
     case EPI_FWD_LOGITS:
-        if (ak && bk) return launch_cfg<D, true, true, EPI_FWD_LOGITS>(a, st);
+        if (a_k && b_k) return launch_cfg<D, true, true, EPI_FWD_LOGITS>(a, st);
         break;
     case EPI_LSE:
-        if (ak && bk) return launch_cfg<D, true, true, EPI_LSE>(a, st);
+        if (a_k && b_k) return launch_cfg<D, true, true, EPI_LSE>(a, st);
         break;
     case EPI_DZ:
-        if (ak && bk) return launch_cfg<D, true, true, EPI_DZ>(a, st);
+        if (a_k && b_k) return launch_cfg<D, true, true, EPI_DZ>(a, st);
         break;
     case EPI_BWD_DATA:
-        if (ak && !bk) return launch_cfg<D, true, false, EPI_BWD_DATA>(a, st);
+        if (a_k && b_n) return launch_cfg<D, true, false, EPI_BWD_DATA>(a, st);
         break;
     case EPI_UPDATE:
-        if (!ak && !bk) return launch_cfg<D, false, false, EPI_UPDATE>(a, st);
+        if (a_m && b_n) return launch_cfg<D, false, false, EPI_UPDATE>(a, st);
         break;
     default: break;
     }

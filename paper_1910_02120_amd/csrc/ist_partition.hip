@@ -419,14 +419,40 @@ __global__ void k_bias_replicate(const E *__restrict__ b, E *__restrict__ sub, i
     for (int g = 0; g < G; ++g) sub[(int64_t)g * n + i] = v;
 }
 
+// Sum of up to 64 values as a balanced pairwise tree over the index (neighbours first, then pairs
+// of pairs, ...); missing leaves are +0, which leaves every partial sum unchanged.
+template <typename F>
+__device__ inline float tree_sum64(int count, F value)
+{
+    float v[64];
+#pragma unroll
+    for (int s = 0; s < 64; ++s) v[s] = s < count ? value(s) : 0.0f;
+#pragma unroll
+    for (int d = 1; d < 64; d *= 2)
+#pragma unroll
+        for (int s = 0; s + d < 64; s += 2 * d) v[s] = v[s] + v[s + d];
+    return v[0];
+}
+
+// b[i] = (pairwise-tree sum over the G subnet copies) * (1/G).  With G a power of two and
+// identical copies every step is exact: merging an untrained partition returns the bias bit for
+// bit.  Two tree levels of 64 cover G <= 4096.
 template <typename D>
 __global__ void k_bias_mean(typename D::T *__restrict__ b, const typename D::T *__restrict__ sub,
                             int64_t n, int32_t G)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    float acc = 0.0f;
-    for (int g = 0; g < G; ++g) acc += D::ld(sub + (int64_t)g * n + i);
+    float acc;
+    if (G <= 64) {
+        acc = tree_sum64(G, [&](int s) { return D::ld(sub + (int64_t)s * n + i); });
+    } else {
+        const int chunks = (G + 63) / 64;
+        acc = tree_sum64(chunks, [&](int c) {
+            const int left = G - 64 * c;
+            return tree_sum64(left < 64 ? left : 64, [&](int s) { return D::ld(sub + (int64_t)(64 * c + s) * n + i); });
+        });
+    }
     b[i] = D::cvt(acc * (1.0f / (float)G));
 }
 

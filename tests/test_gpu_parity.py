@@ -36,6 +36,10 @@ SHAPES = {
     # wide enough for the 256x256 block tiles (forward of layer 1, backward-data of layer 2)
     "big-tiles-bf16": _mk("big-tiles-bf16", "cfg3", dims=(520, 33280, 4352, 10), S=16, B=300, k=2,
                           lr=0.05),
+    # degenerate shapes: one hidden layer and a batch of one sample; a deeper net with S = N_l / 2
+    "one-hidden-B1-f32": _mk("one-hidden-B1-f32", "cfg2", dims=(40, 64, 7), S=4, B=1, k=2, lr=0.05),
+    "deep-bf16": _mk("deep-bf16", "cfg3", dims=(64, 128, 256, 128, 64, 12), S=4, B=20, k=3, lr=0.05),
+    "width-one-blocks-f32": _mk("width-one-blocks-f32", "cfg2", dims=(24, 8, 8, 5), S=8, B=9, k=2, lr=0.05),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
@@ -189,4 +193,28 @@ def test_k_zero_and_empty_step_list():
     for s in range(cfg.S):
         for l in range(cfg.t):
             assert torch.equal(before[s][0][l], after[s][0][l])
+    ctx.close()
+
+
+def test_profile_records_name_kernels_and_work():
+    """Per-kernel profiling records: labels, launch counts and algorithmic flops of a known shape."""
+    cfg = SHAPES["ragged-f32"]
+    P = H.Problem(cfg, dev=_dev())
+    ctx = P.context()
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    ctx.partition(P.dW, P.db, P.dperm)
+    P.gpu_steps(ctx)
+    ctx.merge(P.dW, P.db)
+    ks = ctx.profile_kernels()
+    classes = ctx.profile_read()
+    ctx.profile_enable(False)
+    assert sum(k["launches"] for k in ks) == sum(n for _, n in classes.values())
+    t = cfg.t
+    widths = [cfg.width(l) for l in range(t + 1)]
+    fwd = sum(2.0 * cfg.B * widths[l] * widths[l - 1] * cfg.S for l in range(1, t + 1)) * cfg.k
+    got = sum(k["flops"] for k in ks if k["kernel_class"] == "gemm_forward")
+    assert got == pytest.approx(fwd, rel=1e-12)
+    assert all(k["ms"] > 0 for k in ks)
+    assert any(k["label"].startswith("k_") and k["bytes"] > 0 for k in ks if k["kernel_class"] == "partition_copy")
     ctx.close()

@@ -186,3 +186,45 @@ def test_output_bias_merge_is_the_mean():
     same = [(Wl, [bl[0], b[0]]) for Wl, bl in subs]
     orc.merge(Ws, bs, perms, S, same)
     assert np.array_equal(bs[-1], b[0])
+
+
+def _merge_bias(b):
+    """Output bias the oracle's merge produces from per-subnet copies b [S][n] (float32)."""
+    S, n = b.shape
+    cfg = _cfg((3, 2 * S, n), S)
+    Ws, bs = gen.make_weights(cfg)
+    perms = gen.make_perms(cfg)
+    subs = orc.partition(Ws, bs, perms, S)
+    subs = [(Wl, [bl[0], b[s]]) for s, (Wl, bl) in enumerate(subs)]
+    orc.merge(Ws, bs, perms, S, subs)
+    return bs[-1].astype(np.float32)
+
+
+@pytest.mark.parametrize("S", [2, 8, 16, 64, 128])
+def test_output_bias_round_trip_is_exact_for_power_of_two_S(S):
+    """merge(partition(b_t)) == b_t bit for bit: with identical copies every addition of the
+    pairwise tree doubles its operand and the final scaling by 1/S is a power of two.  (A running
+    sum x, 2x, 3x, ... would round at 3x.)"""
+    rng = np.random.default_rng(S)
+    x = rng.standard_normal(3000).astype(np.float32)
+    got = _merge_bias(np.tile(x, (S, 1)))
+    assert np.array_equal(got.view(np.uint32), x.view(np.uint32))
+
+
+def test_output_bias_tree_shape_for_ragged_S():
+    """The order of the binary32 additions, written out by hand for S = 3, 5, 6, 7."""
+    f = np.float32
+    rng = np.random.default_rng(11)
+    for S in (3, 5, 6, 7):
+        b = (rng.standard_normal((S, 400)) * 10.0 ** rng.integers(-3, 4, (S, 400))).astype(np.float32)
+        v = [b[s] for s in range(S)]
+        if S == 3:
+            tot = (v[0] + v[1]) + v[2]
+        elif S == 5:
+            tot = ((v[0] + v[1]) + (v[2] + v[3])) + v[4]
+        elif S == 6:
+            tot = ((v[0] + v[1]) + (v[2] + v[3])) + (v[4] + v[5])
+        else:
+            tot = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + v[6])
+        want = (tot * (f(1.0) / f(S))).astype(np.float32)
+        assert np.array_equal(_merge_bias(b).view(np.uint32), want.view(np.uint32)), S
