@@ -218,3 +218,62 @@ def test_profile_records_name_kernels_and_work():
     assert all(k["ms"] > 0 for k in ks)
     assert any(k["label"].startswith("k_") and k["bytes"] > 0 for k in ks if k["kernel_class"] == "partition_copy")
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["ragged-f32", "ragged-bf16", "csr-f32"])
+def test_batch_smaller_than_max_B(name):
+    """A context sized for max_B runs smaller batches: same result as a context sized exactly."""
+    from paper_1910_02120_amd import ISTContext
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, dev=_dev())
+    big = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B + 19, device=_dev())
+    big.partition(P.dW, P.db, P.dperm)
+    P.gpu_steps(big)
+    subs = P.oracle_subnets()
+    P.oracle_steps(subs)
+    H.compare_subnets(H.export_all(big, cfg), subs, cfg, H.TOL[cfg.dtype])
+    big.close()
+
+
+def test_csr_with_empty_rows_and_unused_columns():
+    """Samples without non-zeros see the bias only; weights of columns no sample touches stay put."""
+    cfg = SHAPES["csr-f32"]
+    P = H.Problem(cfg, dev=_dev())
+    rows = len(P.rp) - 1
+    keep = np.ones(len(P.ci), dtype=bool)
+    for r in range(0, rows, 5):                      # every fifth sample loses all its features
+        keep[P.rp[r]:P.rp[r + 1]] = False
+    keep &= P.ci % 3 != 0                            # and a third of the columns never appears
+    cnt = np.add.reduceat(keep.astype(np.int64), P.rp[:-1]) * (np.diff(P.rp) > 0)
+    P.rp = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
+    P.ci, P.va = P.ci[keep].copy(), P.va[keep].copy()
+    assert (np.diff(P.rp) == 0).any()
+    P.upload()
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    loss = P.gpu_steps(ctx)
+    subs = P.oracle_subnets()
+    before = [s[0][0].copy() for s in subs]
+    want_loss = P.oracle_steps(subs)
+    got = H.export_all(ctx, cfg)
+    H.compare_subnets(got, subs, cfg, H.TOL[cfg.dtype])
+    np.testing.assert_allclose(loss, want_loss, rtol=1e-2, atol=1e-4)
+    unused = np.arange(cfg.dims[0]) % 3 == 0
+    for s in range(cfg.S):                           # bit-exact: nothing may touch those columns
+        w0 = H.np_bits(before[s].astype(np.float32), cfg.dtype)
+        assert np.array_equal(H.bits(got[s][0][0])[:, unused], w0[:, unused])
+    ctx.close()
+
+
+@pytest.mark.parametrize("dims,S,B", [((12, 16, 1), 4, 6), ((20, 64, 64, 3), 64, 5)])
+def test_single_class_and_as_many_subnets_as_neurons(dims, S, B):
+    cfg = _mk(f"edge-{dims[-1]}-{S}", "cfg2", dims=dims, S=S, B=B, k=2, lr=0.05)
+    P = H.Problem(cfg, dev=_dev())
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    loss = P.gpu_steps(ctx)
+    subs = P.oracle_subnets()
+    want_loss = P.oracle_steps(subs)
+    H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, H.TOL[cfg.dtype])
+    np.testing.assert_allclose(loss, want_loss, rtol=1e-2, atol=1e-5)
+    ctx.close()
