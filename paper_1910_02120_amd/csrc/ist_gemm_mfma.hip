@@ -255,10 +255,10 @@ template <> __device__ inline void pre8_decode<float>(const Pre8<float> &r, floa
 }
 
 // Epilogue for 8 consecutive columns n0..n0+7 of row m (gz: output group index).
-// pre: values fetched ahead for this chunk (used on the 16-byte path only), or null.
-template <typename D, int EPI>
+// pre: values fetched ahead for this chunk (HASPRE; used on the 16-byte path only).
+template <typename D, int EPI, bool HASPRE = false>
 __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, float (&val)[8], bool vecC,
-                            const Pre8<typename D::T> *pre = nullptr)
+                            const Pre8<typename D::T> &pre = Pre8<typename D::T>{})
 {
     using T = typename D::T;
     if (m >= a.M || n0 >= a.N) return;
@@ -287,12 +287,12 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
     }
     float o[8];
     if (EPI == EPI_BWD_DATA) {
-        if (pre && vec) pre8_decode<T>(*pre, o);
+        if (HASPRE && vec) pre8_decode<T>(pre, o);
         else Row8<T>::ld(static_cast<const T *>(a.mask) + (int64_t)g * a.gMask + (int64_t)m * a.ldm + n0, vec, nv, o);
 #pragma unroll
         for (int i = 0; i < 8; ++i) val[i] = o[i] > 0.0f ? val[i] : 0.0f;
     } else {   // EPI_UPDATE
-        if (pre && vec) pre8_decode<T>(*pre, o);
+        if (HASPRE && vec) pre8_decode<T>(pre, o);
         else Row8<T>::ld(static_cast<const T *>(a.C) + ci, vec, nv, o);
 #pragma unroll
         for (int i = 0; i < 8; ++i) val[i] = o[i] - a.lr * val[i];
@@ -527,14 +527,18 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
                 compute(cur, cur + TA::ELEMS);
                 __syncthreads();
             };
-            int it0 = 0;
-            for (; it0 + U <= ntile; it0 += U) {
+            if (ST == 1 && TM * TN >= 8) {   // register-bound tiles: one copy of the loop body, LDS buffer chosen at run time
+                for (int it = 0; it < ntile; ++it) step(it, it & 1);
+            } else {
+                int it0 = 0;
+                for (; it0 + U <= ntile; it0 += U) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) step(it0 + u, u);
+                    for (int u = 0; u < U; ++u) step(it0 + u, u);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (it0 + u < ntile) step(it0 + u, u);
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (it0 + u < ntile) step(it0 + u, u);
         } else {
         // Main loop: whole groups of ST tiles, no branch around any load (loads past the
         // end of k are masked, not skipped), so the wait counters stay exact.
@@ -677,8 +681,8 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
                     else if (EPI == EPI_DZ)
                         epi_dz<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, lab[i][p], lsv[i][p]);
                     else
-                        epi8<D, EPI>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
-                                     val, vecC, PRE ? &pre[i % PD][p] : nullptr);
+                        epi8<D, EPI, PRE>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
+                                          val, vecC, pre[i % PD][p]);
                 }
             }
             if (PRE && i + PD < TM) preload(i + PD, pre[i % PD]);
