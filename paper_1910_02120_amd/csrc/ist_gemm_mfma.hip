@@ -256,9 +256,10 @@ template <> __device__ inline void pre8_decode<float>(const Pre8<float> &r, floa
 
 // Epilogue for 8 consecutive columns n0..n0+7 of row m (gz: output group index).
 // pre: values fetched ahead for this chunk (HASPRE; used on the 16-byte path only).
+// bias8: the bias of these 8 columns (zeros without bias), fetched once per tile by the caller.
 template <typename D, int EPI, bool HASPRE = false>
 __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, float (&val)[8], bool vecC,
-                            const Pre8<typename D::T> &pre = Pre8<typename D::T>{})
+                            const float (&bias8)[8], const Pre8<typename D::T> &pre = Pre8<typename D::T>{})
 {
     using T = typename D::T;
     if (m >= a.M || n0 >= a.N) return;
@@ -270,12 +271,8 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
         return;
     }
     if (EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS) {
-        if (a.bias) {
-            float b[8];
-            Row8<T>::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n0, vec, nv, b);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) val[i] += b[i];
-        }
+        for (int i = 0; i < 8; ++i) val[i] += bias8[i];
         if (EPI == EPI_FWD_RELU) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) val[i] = val[i] > 0.0f ? val[i] : 0.0f;
@@ -304,18 +301,14 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
 // EPI_LSE: the CPR lanes that hold the 8-column chunks of one row of the wave's column block
 // reduce max and sum(exp) of that block; logits are not stored.  All lanes take part.
 template <typename D, int CPR>
-__device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk, float (&val)[8], bool vecBias,
-                               int label)
+__device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk, float (&val)[8],
+                               const float (&bias8)[8], int label)
 {
     using T = typename D::T;
     const bool rowok = m < a.M;
     const int nv = !rowok ? 0 : (a.N - n0 >= 8 ? 8 : (a.N - n0 > 0 ? a.N - n0 : 0));
-    if (a.bias && nv > 0) {
-        float b[8];
-        Row8<T>::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n0, vecBias && nv == 8, nv, b);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) val[i] += b[i];
-    }
+    for (int i = 0; i < 8; ++i) val[i] += bias8[i];
     // exp(x) = exp2(x * log2(e)): scale once, then only v_exp_f32 per element
     constexpr float kLog2e = 1.4426950408889634f;
     float mx = -INFINITY, se = 0.0f;
@@ -352,19 +345,15 @@ __device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk,
 
 // EPI_DZ: dz[m][n] = (exp(z - lse_m) - [n == y_m]) / B, stored in the storage dtype.
 template <typename D>
-__device__ inline void epi_dz(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC, int label,
-                              float lse)
+__device__ inline void epi_dz(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC,
+                              const float (&bias8)[8], int label, float lse)
 {
     using T = typename D::T;
     if (m >= a.M || n0 >= a.N) return;
     const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
     const bool vec = vecC && nv == 8;
-    if (a.bias) {
-        float b[8];
-        Row8<T>::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n0, vec, nv, b);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) val[i] += b[i];
-    }
+    for (int i = 0; i < 8; ++i) val[i] += bias8[i];
     constexpr float kLog2e = 1.4426950408889634f;
     const float ls = lse * kLog2e;
 #pragma unroll
@@ -611,6 +600,15 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
         constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
         constexpr int RPP = 64 / CPR;      // rows per pass
         // per-row inputs of the cross-entropy epilogues, fetched in one batch up front
+        // the 8 columns a lane finishes are the same in every row slice: one bias fetch per tile
+        float bias8[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        if ((EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS || EPI == EPI_LSE || EPI == EPI_DZ) && a.bias) {
+            const int n = cn0 + wn + 8 * (lane % CPR);
+            const int nv = a.N - n >= 8 ? 8 : (a.N - n > 0 ? a.N - n : 0);
+            if (nv > 0)
+                Row8<typename D::T>::ld(static_cast<const typename D::T *>(a.bias) + (int64_t)cg * a.gBias + n,
+                                        vecC && nv == 8, nv, bias8);
+        }
         int lab[TM][32 / RPP];
         float lsv[TM][32 / RPP];
         if (EPI == EPI_LSE || EPI == EPI_DZ) {
@@ -676,13 +674,13 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
                     const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
                     float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
                     if (EPI == EPI_LSE)
-                        epi_lse<D, CPR>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, (cn0 + wn) / (32 * TN), val, vecC,
+                        epi_lse<D, CPR>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, (cn0 + wn) / (32 * TN), val, bias8,
                                         lab[i][p]);
                     else if (EPI == EPI_DZ)
-                        epi_dz<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, lab[i][p], lsv[i][p]);
+                        epi_dz<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, bias8, lab[i][p], lsv[i][p]);
                     else
                         epi8<D, EPI, PRE>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
-                                          val, vecC, pre[i % PD][p]);
+                                          val, vecC, bias8, pre[i % PD][p]);
                 }
             }
             if (PRE && i + PD < TM) preload(i + PD, pre[i % PD]);
@@ -713,7 +711,11 @@ __global__ __launch_bounds__(256) void k_splitk_finish(GemmArgs a, const float *
 #pragma unroll
         for (int i = 0; i < 8; ++i) val[i] += t[i];
     }
-    epi8<D, EPI>(a, g, g, m, n0, val, vecC);
+    float bias8[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    if ((EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS) && a.bias)
+        Row8<typename D::T>::ld(static_cast<const typename D::T *>(a.bias) + (int64_t)g * a.gBias + n0, vecC && nv == 8, nv,
+                                bias8);
+    epi8<D, EPI>(a, g, g, m, n0, val, vecC, bias8);
 }
 
 // 16-byte loads need an aligned base and group stride and a pitch that is a multiple
