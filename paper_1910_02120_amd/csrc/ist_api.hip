@@ -437,11 +437,8 @@ ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *
         IST_RUN(KC_PARTITION_COPY, launch_partition_copy(a, st), "partition copy");
         if (ctx->has_bias) {
             if (l < t) {
-                CopyArgs b{};
-                b.W = params->b[l - 1]; b.ld = 1; b.sub = ctx->subnets + L.off_b;
-                b.rows = a.rows; b.cols = nullptr; b.nr = L.R; b.nc = 1; b.G = S; b.esz = e;
-                b.N_out = L.N_out; b.N_in = 1; b.transposed = false;
-                IST_RUN(KC_BIAS_COPY, launch_partition_copy(b, st), "partition bias");
+                IST_RUN(KC_BIAS_COPY, launch_bias_rows(params->b[l - 1], ctx->subnets + L.off_b, a.rows, L.R * S, e, false, st),
+                        "partition bias");
             } else {
                 IST_RUN(KC_BIAS_COPY, launch_bias_replicate(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, e, st),
                         "replicate output bias");
@@ -466,11 +463,8 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream)
         IST_RUN(KC_MERGE_COPY, launch_merge_copy(a, st), "merge copy");
         if (ctx->has_bias) {
             if (l < t) {
-                CopyArgs b{};
-                b.W = params->b[l - 1]; b.ld = 1; b.sub = ctx->subnets + L.off_b;
-                b.rows = a.rows; b.cols = nullptr; b.nr = L.R; b.nc = 1; b.G = S; b.esz = e;
-                b.N_out = L.N_out; b.N_in = 1; b.transposed = false;
-                IST_RUN(KC_BIAS_COPY, launch_merge_copy(b, st), "merge bias");
+                IST_RUN(KC_BIAS_COPY, launch_bias_rows(params->b[l - 1], ctx->subnets + L.off_b, a.rows, L.R * S, e, true, st),
+                        "merge bias");
             } else {
                 IST_RUN(KC_BIAS_COPY, launch_bias_mean(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, ctx->dtype, st),
                         "mean output bias");

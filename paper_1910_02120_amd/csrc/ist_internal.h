@@ -135,6 +135,8 @@ struct CopyArgs {
 };
 hipError_t launch_partition_copy(const CopyArgs &a, hipStream_t st);
 hipError_t launch_merge_copy(const CopyArgs &a, hipStream_t st);
+hipError_t launch_bias_rows(void *b, void *sub, const int32_t *rows, int64_t n, int esz, bool scatter,
+                            hipStream_t st);
 hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G, int esz,
                                  hipStream_t st);
 hipError_t launch_bias_mean(void *b, const void *sub, int64_t n, int32_t G, int dtype,

@@ -31,8 +31,10 @@ __global__ void k_perm_check(const int32_t *__restrict__ perm, const int32_t *__
     if (p < 0 || p >= N || perm[p] != (int32_t)c) atomicOr(err, 2);
 }
 
-// One workgroup per subnet s: walk neuron ids c in ascending order, keep those
-// whose perm position lies in block s, and number them (ordered compaction).
+// Ordered compaction of the neuron ids whose perm position lies in block s.  Workgroup
+// (chunk j, subnet s) handles ids [1024 j, 1024 (j+1)): it first counts the members of s among
+// all smaller ids (coalesced reads of the 4-byte table, no barrier inside the loop), which gives
+// the packed position of its first member without any dependence on other workgroups.
 constexpr int kSortThreads = 1024;
 __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
     const int32_t *__restrict__ invpos, int64_t N, int64_t w, int32_t *__restrict__ sorted,
@@ -40,47 +42,47 @@ __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
     int32_t *__restrict__ rank, int64_t words)
 {
     __shared__ int32_t wave_cnt[kSortThreads / 64];
-    __shared__ int32_t base_sh;
-    const int s = blockIdx.x;
+    __shared__ int32_t wave_pre[kSortThreads / 64];
+    const int s = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) base_sh = 0;
+    const int64_t c0 = (int64_t)blockIdx.x * kSortThreads;
+    const int64_t p_lo = (int64_t)s * w, p_hi = p_lo + w;
+    int cnt = 0;
+    for (int64_t c = threadIdx.x; c < c0; c += kSortThreads) {
+        const int32_t p = invpos[c];
+        cnt += (p >= p_lo && p < p_hi) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    const int64_t c = c0 + threadIdx.x;
+    const int32_t p = (c < N) ? invpos[c] : -1;
+    const bool mine = p >= p_lo && p < p_hi;
+    const unsigned long long bal = __ballot(mine);
+    const int prefix = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) { wave_pre[wave] = cnt; wave_cnt[wave] = __popcll(bal); }
     __syncthreads();
-    for (int64_t c0 = 0; c0 < N; c0 += kSortThreads) {
-        int64_t c = c0 + threadIdx.x;
-        int32_t p = (c < N) ? invpos[c] : -1;
-        bool mine = (p >= 0) && (p < N) && (p / w == s);
-        unsigned long long bal = __ballot(mine);
-        int prefix = __popcll(bal & ((1ull << lane) - 1ull));
-        if (lane == 0) wave_cnt[wave] = __popcll(bal);
-        __syncthreads();
-        int before = 0, total = 0;
-        for (int i = 0; i < kSortThreads / 64; ++i) {
-            int v = wave_cnt[i];
-            before += (i < wave) ? v : 0;
-            total += v;
+    int base = 0, before = 0;
+    for (int i = 0; i < kSortThreads / 64; ++i) {
+        base += wave_pre[i];
+        before += (i < wave) ? wave_cnt[i] : 0;
+    }
+    if (lane == 0) {   // membership bitmask and prefix counts of these 64 neuron ids
+        const int64_t w0 = (c0 + (int64_t)wave * 64) >> 5;
+        const uint32_t lo = (uint32_t)bal, hi = (uint32_t)(bal >> 32);
+        if (w0 < words) { mask[(int64_t)s * words + w0] = lo; rank[(int64_t)s * words + w0] = base + before; }
+        if (w0 + 1 < words) {
+            mask[(int64_t)s * words + w0 + 1] = hi;
+            rank[(int64_t)s * words + w0 + 1] = base + before + __popc(lo);
         }
-        int base = base_sh;
-        if (lane == 0) {   // membership bitmask and prefix counts of these 64 neuron ids
-            const int64_t w0 = (c0 + (int64_t)wave * 64) >> 5;
-            const uint32_t lo = (uint32_t)bal, hi = (uint32_t)(bal >> 32);
-            if (w0 < words) { mask[(int64_t)s * words + w0] = lo; rank[(int64_t)s * words + w0] = base + before; }
-            if (w0 + 1 < words) {
-                mask[(int64_t)s * words + w0 + 1] = hi;
-                rank[(int64_t)s * words + w0 + 1] = base + before + __popc(lo);
-            }
+    }
+    if (mine) {
+        const int64_t q = (int64_t)base + before + prefix;
+        if (q < w) {   // always true for a valid permutation
+            const int64_t P = p_lo + q;
+            sorted[P] = (int32_t)c;
+            slot[c] = (int32_t)P;
+            p2q[p] = (int32_t)P;
         }
-        if (mine) {
-            int64_t q = (int64_t)base + before + prefix;
-            if (q < w) {   // always true for a valid permutation
-                int64_t P = (int64_t)s * w + q;
-                sorted[P] = (int32_t)c;
-                slot[c] = (int32_t)P;
-                p2q[p] = (int32_t)P;
-            }
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) base_sh = base + total;
-        __syncthreads();
     }
 }
 
@@ -91,8 +93,8 @@ hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t
     const int th = 256;
     const unsigned nb = (unsigned)((N + th - 1) / th);
     hipLaunchKernelGGL(k_perm_invert, dim3(nb), dim3(th), 0, st, perm, N, invpos, err);
-    hipLaunchKernelGGL(k_perm_sort, dim3(S), dim3(kSortThreads), 0, st, invpos, N, N / S, sorted,
-                       slot, p2q, mask, rank, (N + 31) / 32);
+    hipLaunchKernelGGL(k_perm_sort, dim3((unsigned)((N + kSortThreads - 1) / kSortThreads), (unsigned)S),
+                       dim3(kSortThreads), 0, st, invpos, N, N / S, sorted, slot, p2q, mask, rank, (N + 31) / 32);
     return hipGetLastError();
 }
 
@@ -454,6 +456,28 @@ __global__ void k_bias_mean(typename D::T *__restrict__ b, const typename D::T *
         });
     }
     b[i] = D::cvt(acc * (1.0f / (float)G));
+}
+
+// hidden biases travel with their neuron: sub[P] <-> b[rows[P]]
+template <typename E, bool SCATTER>
+__global__ void k_bias_rows(E *__restrict__ b, E *__restrict__ sub, const int32_t *__restrict__ rows, int64_t n)
+{
+    const int64_t P = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (P >= n) return;
+    if (SCATTER) b[rows[P]] = sub[P]; else sub[P] = b[rows[P]];
+}
+
+hipError_t launch_bias_rows(void *b, void *sub, const int32_t *rows, int64_t n, int esz, bool scatter, hipStream_t st)
+{
+    const dim3 grid((unsigned)((n + 255) / 256));
+    if (esz == 2) {
+        if (scatter) hipLaunchKernelGGL((k_bias_rows<uint16_t, true>), grid, dim3(256), 0, st, (uint16_t *)b, (uint16_t *)sub, rows, n);
+        else hipLaunchKernelGGL((k_bias_rows<uint16_t, false>), grid, dim3(256), 0, st, (uint16_t *)b, (uint16_t *)sub, rows, n);
+    } else {
+        if (scatter) hipLaunchKernelGGL((k_bias_rows<uint32_t, true>), grid, dim3(256), 0, st, (uint32_t *)b, (uint32_t *)sub, rows, n);
+        else hipLaunchKernelGGL((k_bias_rows<uint32_t, false>), grid, dim3(256), 0, st, (uint32_t *)b, (uint32_t *)sub, rows, n);
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G, int esz,
