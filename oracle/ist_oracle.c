@@ -144,12 +144,48 @@ void ist_oracle_merge_out_bias(const double *bsub /* [S][n] */, int32_t S, int64
  * w <- w - eta * grad.  dh_{l-1} is formed with the weights before their update.
  * Returns 0, or -1 on a bad argument.
  */
+int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, double **b,
+                                   int32_t is_csr, const double *X, const int32_t *rowptr,
+                                   const int32_t *colidx, const double *vals, const int32_t *y,
+                                   int32_t B, int32_t k, double lr, int32_t mode, int32_t normalize,
+                                   double eps, double *loss_out);
+
 int32_t ist_oracle_subnet_sgd(int32_t t, const int64_t *n, double **W, double **b,
                               int32_t is_csr, const double *X, const int32_t *rowptr,
                               const int32_t *colidx, const double *vals, const int32_t *y,
                               int32_t B, int32_t k, double lr, int32_t mode, double *loss_out)
 {
+    return ist_oracle_subnet_sgd_norm(t, n, W, b, is_csr, X, rowptr, colidx, vals, y, B, k, lr, mode, 0, 0.0,
+                                      loss_out);
+}
+
+/*
+ * The same with the correction of Section 2.2 ("Correcting Distributional Shift"):
+ * with normalize != 0 every hidden neuron's input is standardised over the mini-batch
+ * before the activation,
+ *     mu_r = mean_b z[b][r],  sigma_r = sqrt(mean_b (z[b][r] - mu_r)^2 + eps),
+ *     zh = (z - mu) / sigma,  h = ReLU(zh),
+ * (no n^2 factor, no learned scale or shift; the statistics are those of the batch
+ * and the gradient flows through them, as in batch normalisation, to which the
+ * paper likens the step).  Back-propagation through the standardisation:
+ *     dz = (dzh - mean_b dzh - zh * mean_b(dzh * zh)) / sigma,   dzh = dh * [zh > 0].
+ * Storage rounding (mode 1/2): zh and dzh and dz are rounded where they are stored;
+ * z, mu, sigma are not.
+ */
+int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, double **b,
+                                   int32_t is_csr, const double *X, const int32_t *rowptr,
+                                   const int32_t *colidx, const double *vals, const int32_t *y,
+                                   int32_t B, int32_t k, double lr, int32_t mode, int32_t normalize,
+                                   double eps, double *loss_out)
+{
     if (t < 1 || B <= 0 || k < 0) return -1;
+    double **zh = (double **)calloc((size_t)t + 1, sizeof(double *));
+    double **isg = (double **)calloc((size_t)t + 1, sizeof(double *));
+    if (normalize)
+        for (int32_t l = 1; l < t; ++l) {
+            zh[l] = (double *)malloc(sizeof(double) * (size_t)B * (size_t)n[l]);
+            isg[l] = (double *)malloc(sizeof(double) * (size_t)n[l]);
+        }
     /* activations h[l] [B][n_l] for l = 1..t-1, logits z [B][n_t], gradients */
     double **h = (double **)calloc((size_t)t + 1, sizeof(double *));
     double **dz = (double **)calloc((size_t)t + 1, sizeof(double *));
@@ -185,8 +221,28 @@ int32_t ist_oracle_subnet_sgd(int32_t t, const int64_t *n, double **W, double **
                     for (int64_t c = 0; c < nin; ++c) acc += hr[c] * wr[c];
                 }
                 if (bl) acc += bl[r];
-                if (l < t) acc = round_store(acc > 0.0 ? acc : 0.0, mode);
-                hout[bi * nout + r] = acc; /* logits stay unrounded */
+                if (l < t && !normalize) acc = round_store(acc > 0.0 ? acc : 0.0, mode);
+                hout[bi * nout + r] = acc; /* logits (and inputs of the standardisation) stay unrounded */
+            }
+            if (l < t && normalize) {
+#pragma omp parallel for schedule(static)
+                for (int64_t r = 0; r < nout; ++r) {
+                    double mu = 0.0, var = 0.0;
+                    for (int64_t bi = 0; bi < B; ++bi) mu += hout[bi * nout + r];
+                    mu /= (double)B;
+                    for (int64_t bi = 0; bi < B; ++bi) {
+                        double d = hout[bi * nout + r] - mu;
+                        var += d * d;
+                    }
+                    var /= (double)B;
+                    double inv = 1.0 / sqrt(var + eps);
+                    isg[l][r] = inv;
+                    for (int64_t bi = 0; bi < B; ++bi) {
+                        double v = round_store((hout[bi * nout + r] - mu) * inv, mode);
+                        zh[l][bi * nout + r] = v;
+                        hout[bi * nout + r] = v > 0.0 ? v : 0.0;
+                    }
+                }
             }
         }
 
@@ -238,6 +294,23 @@ int32_t ist_oracle_subnet_sgd(int32_t t, const int64_t *n, double **W, double **
                     for (int64_t c = 0; c < nin; ++c)
                         row[c] = round_store(hprev[bi * nin + c] > 0.0 ? row[c] : 0.0, mode);
                 }
+                if (normalize) {
+                    const double *zz = zh[l - 1];
+                    const double *inv = isg[l - 1];
+#pragma omp parallel for schedule(static)
+                    for (int64_t c = 0; c < nin; ++c) {
+                        double s1 = 0.0, s2 = 0.0;
+                        for (int64_t bi = 0; bi < B; ++bi) {
+                            s1 += gp[bi * nin + c];
+                            s2 += gp[bi * nin + c] * zz[bi * nin + c];
+                        }
+                        s1 /= (double)B;
+                        s2 /= (double)B;
+                        for (int64_t bi = 0; bi < B; ++bi)
+                            gp[bi * nin + c] = round_store(
+                                (gp[bi * nin + c] - s1 - zz[bi * nin + c] * s2) * inv[c], mode);
+                    }
+                }
             }
 
             /* dW_l = dz_l^T h_{l-1};  W_l <- W_l - lr dW_l;  b_l <- b_l - lr sum_b dz_l */
@@ -284,7 +357,7 @@ int32_t ist_oracle_subnet_sgd(int32_t t, const int64_t *n, double **W, double **
         }
     }
 
-    for (int32_t l = 1; l <= t; ++l) { free(h[l]); free(dz[l]); }
-    free(h); free(dz); free(rowloss);
+    for (int32_t l = 1; l <= t; ++l) { free(h[l]); free(dz[l]); free(zh[l]); free(isg[l]); }
+    free(h); free(dz); free(zh); free(isg); free(rowloss);
     return 0;
 }

@@ -69,6 +69,10 @@ def _load():
         fn.argtypes = [p, C.c_int64, C.c_int64, p, C.c_int64, p, C.c_int64, p]
     lib.ist_oracle_merge_out_bias.restype = None
     lib.ist_oracle_merge_out_bias.argtypes = [p, C.c_int32, C.c_int64, C.c_int32, p]
+    lib.ist_oracle_subnet_sgd_norm.restype = C.c_int32
+    lib.ist_oracle_subnet_sgd_norm.argtypes = [C.c_int32, p, p, p, C.c_int32, p, p, p, p, p,
+                                               C.c_int32, C.c_int32, C.c_double, C.c_int32, C.c_int32,
+                                               C.c_double, p]
     lib.ist_oracle_subnet_sgd.restype = C.c_int32
     lib.ist_oracle_subnet_sgd.argtypes = [C.c_int32, p, p, p, C.c_int32, p, p, p, p, p,
                                           C.c_int32, C.c_int32, C.c_double, C.c_int32, p]
@@ -177,10 +181,15 @@ def merge(Ws, bs, perms, S: int, subs, mode: str = "f32") -> None:
 
 
 # ------------------------------------------------------------------ training
+NORM_EPS = 1e-5   # epsilon under the square root of the per-neuron standardisation
+
+
 def subnet_sgd(Wl: List[np.ndarray], bl: Optional[List[Optional[np.ndarray]]], y: np.ndarray,
-               lr: float, k: int, mode: str, X: Optional[np.ndarray] = None, csr=None):
+               lr: float, k: int, mode: str, X: Optional[np.ndarray] = None, csr=None,
+               normalize: bool = False, eps: float = NORM_EPS):
     """k local SGD steps on one subnet.  Wl/bl are float64 arrays updated in place.
     X: [k][B][n_0] float64, or csr = (rowptr[k*B+1], colidx, vals float64).
+    normalize: standardise every hidden neuron's input over the mini-batch (Section 2.2).
     Returns loss[k]."""
     t = len(Wl)
     for w in Wl:
@@ -210,8 +219,9 @@ def subnet_sgd(Wl: List[np.ndarray], bl: Optional[List[Optional[np.ndarray]]], y
         assert rp.shape[0] == k * B + 1
         assert ci.size == 0 or (ci.min() >= 0 and ci.max() < n[0])
         args = (1, None, _ptr(rp), _ptr(ci), _ptr(va))
-    rc = _load().ist_oracle_subnet_sgd(t, _ptr(n), Wp, bp, *args, _ptr(y), B, k,
-                                       float(np.float32(lr)), MODE[mode], _ptr(loss))
+    rc = _load().ist_oracle_subnet_sgd_norm(t, _ptr(n), Wp, bp, *args, _ptr(y), B, k,
+                                            float(np.float32(lr)), MODE[mode], 1 if normalize else 0,
+                                            float(eps), _ptr(loss))
     if rc:
         raise ValueError("ist_oracle_subnet_sgd rejected its arguments")
     return loss
@@ -224,7 +234,7 @@ def csr_slice(rowptr, colidx, vals, r0: int, r1: int):
 
 
 def subnet_steps(subs_f64, lr: float, k: int, mode: str, y: np.ndarray,
-                 X: Optional[np.ndarray] = None, csr=None):
+                 X: Optional[np.ndarray] = None, csr=None, normalize: bool = False):
     """Local SGD on every subnet independently (no communication between them).
     subs_f64[s] = (W list, b list) in float64, updated in place; X [S][k][B][N_0]
     or a CSR whose row (s*k + j)*B + b is sample b of step j of subnet s.
@@ -235,9 +245,9 @@ def subnet_steps(subs_f64, lr: float, k: int, mode: str, y: np.ndarray,
     for s in range(S):
         Wl, bl = subs_f64[s]
         if csr is None:
-            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, X=X[s, :k])
+            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, X=X[s, :k], normalize=normalize)
         else:
-            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode,
+            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, normalize=normalize,
                                    csr=csr_slice(*csr, s * y.shape[1] * B, (s * y.shape[1] + k) * B))
     return losses
 
