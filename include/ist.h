@@ -56,6 +56,12 @@ typedef struct {
     int32_t dtype;         /* ist_dtype: storage of W, b, activations, inputs */
     int32_t input;         /* ist_input_kind of the mini-batches */
     int32_t has_bias;      /* 1: biases b_1..b_t exist, 0: none */
+    int32_t normalize;     /* 1: Section 2.2 "Correcting Distributional Shift": every hidden neuron's input
+                              is standardised over the mini-batch before the activation, z <- (z - mu) / sigma
+                              with mu, sigma^2 the mean and (biased) variance over the B samples of the step,
+                              sigma = sqrt(var + norm_eps); the gradient flows through mu and sigma.  0: plain
+                              ReLU network. */
+    float norm_eps;        /* > 0; values <= 0 select 1e-5 */
 } ist_model_desc;
 
 /* Full parameters, caller-owned. [host struct, device arrays] */

@@ -36,7 +36,8 @@ class ISTError(RuntimeError):
 
 class _ModelDesc(C.Structure):
     _fields_ = [("t", C.c_int32), ("dims", C.POINTER(C.c_int64)), ("S", C.c_int32),
-                ("dtype", C.c_int32), ("input", C.c_int32), ("has_bias", C.c_int32)]
+                ("dtype", C.c_int32), ("input", C.c_int32), ("has_bias", C.c_int32),
+                ("normalize", C.c_int32), ("norm_eps", C.c_float)]
 
 
 class _Params(C.Structure):
@@ -108,7 +109,7 @@ class ISTContext:
 
     def __init__(self, dims: Sequence[int], S: int, dtype: str = "f32", input: str = "dense",
                  has_bias: bool = True, max_B: int = 128, device: str = "cuda:0",
-                 bind: bool = True):
+                 bind: bool = True, normalize: bool = False, norm_eps: float = 0.0):
         self.lib = load_library()
         self.dims = [int(d) for d in dims]
         self.t = len(self.dims) - 1
@@ -116,7 +117,9 @@ class ISTContext:
         self.device = torch.device(device)
         self._dims_arr = (C.c_int64 * len(self.dims))(*self.dims)
         desc = _ModelDesc(self.t, self._dims_arr, self.S, IST_BF16 if dtype == "bf16" else IST_F32,
-                          IST_CSR if input == "csr" else IST_DENSE, 1 if has_bias else 0)
+                          IST_CSR if input == "csr" else IST_DENSE, 1 if has_bias else 0,
+                          1 if normalize else 0, float(norm_eps))
+        self.normalize = bool(normalize)
         self._ctx = C.c_void_p()
         st = self.lib.ist_create(C.byref(desc), int(max_B), C.byref(self._ctx))
         if st != IST_OK:

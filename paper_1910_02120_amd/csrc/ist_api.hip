@@ -47,7 +47,7 @@ namespace {
 
 const char *kClassNames[KC_COUNT] = {
     "perm_tables", "partition_copy", "merge_copy", "bias_copy", "gemm_forward", "gemm_backward_data",
-    "gemm_update", "softmax_xent", "loss_reduce", "bias_update", "csr_forward", "csr_update"};
+    "gemm_update", "softmax_xent", "loss_reduce", "bias_update", "csr_forward", "csr_update", "norm"};
 
 hipEvent_t prof_event(ist_ctx *ctx)
 {
@@ -140,7 +140,8 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     if (!d || !out || !d->dims) return IST_EINVAL;
     *out = nullptr;
     if (d->t < 2 || d->S < 1 || (d->dtype != IST_F32 && d->dtype != IST_BF16) ||
-        (d->input != IST_DENSE && d->input != IST_CSR) || (d->has_bias != 0 && d->has_bias != 1))
+        (d->input != IST_DENSE && d->input != IST_CSR) || (d->has_bias != 0 && d->has_bias != 1) ||
+        (d->normalize != 0 && d->normalize != 1) || !(d->norm_eps == d->norm_eps))
         return IST_EINVAL;
     if (max_B < 1) return IST_ESHAPE;
     if (d->S > 4096) return IST_EUNSUPPORTED;   // the output-bias mean is a two-level tree of 64
@@ -152,6 +153,7 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     if (!ctx) return IST_ENOMEM;
     ctx->t = d->t; ctx->S = d->S; ctx->dtype = d->dtype; ctx->input = d->input;
     ctx->has_bias = d->has_bias; ctx->max_B = max_B;
+    ctx->normalize = d->normalize; ctx->norm_eps = d->norm_eps > 0.0f ? d->norm_eps : 1e-5f;
     ctx->dims.assign(d->dims, d->dims + d->t + 1);
     const int t = d->t, S = d->S, e = ctx->esz();
 
@@ -200,6 +202,11 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         if (l == t && ctx->fused_out) act_e = 0;   // logits of a wide output layer are never stored
         L.off_act = w; w = align_up(w + (size_t)S * max_B * L.ldr * act_e);
         L.off_dz = w;  w = align_up(w + (size_t)S * max_B * L.ldr * e);
+        if (ctx->normalize && l < t) {
+            L.off_z = w;   w = align_up(w + (size_t)S * max_B * L.ldr * sizeof(float));
+            L.off_zh = w;  w = align_up(w + (size_t)S * max_B * L.ldr * e);
+            L.off_isg = w; w = align_up(w + (size_t)S * L.ldr * sizeof(float));
+        }
     }
     if (ctx->fused_out) {
         ctx->nb_max = (int32_t)((ctx->dims[t] + 31) / 32);
@@ -525,7 +532,13 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             const void *bias = ctx->has_bias ? sb + L.off_b : nullptr;
             if (l == 1 && csr) {
                 CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R, L.ldr};
-                IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act, dt, st), "csr forward");
+                const bool nrm = ctx->normalize && l < t;
+                IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act,
+                                           nrm ? reinterpret_cast<float *>(ws + L.off_z) : nullptr, dt, st), "csr forward");
+                if (nrm)
+                    IST_RUN(KC_NORM, launch_norm_forward(reinterpret_cast<const float *>(ws + L.off_z), ws + L.off_zh,
+                                        ws + L.off_act, reinterpret_cast<float *>(ws + L.off_isg), S, B, L.R, L.ldr,
+                                        ctx->norm_eps, dt, st), "standardise (forward)");
                 continue;
             }
             GemmArgs a{};
@@ -562,6 +575,15 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_DZ, a, st), "forward gemm (dz)");
                 continue;
             }
+            if (ctx->normalize && l < t) {
+                // z_l in fp32, then standardise each neuron over the batch and apply the ReLU
+                a.C = ws + L.off_z;
+                IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_FWD_LOGITS, a, st), "forward gemm (pre-activation)");
+                IST_RUN(KC_NORM, launch_norm_forward(reinterpret_cast<const float *>(ws + L.off_z), ws + L.off_zh,
+                                    ws + L.off_act, reinterpret_cast<float *>(ws + L.off_isg), S, B, L.R, L.ldr,
+                                    ctx->norm_eps, dt, st), "standardise (forward)");
+                continue;
+            }
             IST_RUN(KC_GEMM_FWD, launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
         }
         // ---------------- loss and dz_t ----------------
@@ -587,6 +609,10 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
                 a.mask = ws + P.off_act; a.ldm = P.ldr; a.gMask = (int64_t)B * P.ldr;
                 IST_RUN(KC_GEMM_BWD_DATA, launch_gemm(dt, EPI_BWD_DATA, a, st), "backward-data gemm");
+                if (ctx->normalize)   // what the product left is d loss / d zh_{l-1}: back through the standardisation
+                    IST_RUN(KC_NORM, launch_norm_backward(ws + P.off_dz, ws + P.off_zh,
+                                        reinterpret_cast<const float *>(ws + P.off_isg), S, B, P.R, P.ldr, dt, st),
+                            "standardise (backward)");
             }
             if (l == 1 && csr) {
                 CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R, L.ldr};

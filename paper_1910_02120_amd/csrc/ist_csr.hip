@@ -16,7 +16,7 @@ namespace ist {
 template <typename D>
 __global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D::T *__restrict__ Wt,
                                                      const typename D::T *__restrict__ bias,
-                                                     typename D::T *__restrict__ h)
+                                                     typename D::T *__restrict__ h, float *__restrict__ z_out)
 {
     using T = typename D::T;
     const int g = blockIdx.z, b = blockIdx.y;
@@ -35,7 +35,8 @@ __global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D
         acc = fmaf(D::up(vals[p]), D::ld(Wg + (int64_t)col * c.w + q), acc);
     }
     if (bias) acc += D::ld(bias + (int64_t)g * c.w + q);
-    h[((int64_t)g * c.B + b) * c.ld + q] = D::cvt(acc > 0.0f ? acc : 0.0f);
+    if (z_out) z_out[((int64_t)g * c.B + b) * c.ld + q] = acc;
+    else h[((int64_t)g * c.B + b) * c.ld + q] = D::cvt(acc > 0.0f ? acc : 0.0f);
 }
 
 __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
@@ -123,17 +124,17 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
     }
 }
 
-hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, int dtype,
+hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out, int dtype,
                               hipStream_t st)
 {
     int th = c.w >= 256 ? 256 : (c.w > 64 ? 128 : 64);
     dim3 grid((unsigned)((c.w + th - 1) / th), (unsigned)c.B, (unsigned)c.G);
     if (dtype == IST_BF16)
         hipLaunchKernelGGL(k_csr_forward<BF16>, grid, dim3(th), 0, st, c, (const uint16_t *)Wt,
-                           (const uint16_t *)bias, (uint16_t *)h);
+                           (const uint16_t *)bias, (uint16_t *)h, z_out);
     else
         hipLaunchKernelGGL(k_csr_forward<F32>, grid, dim3(th), 0, st, c, (const float *)Wt,
-                           (const float *)bias, (float *)h);
+                           (const float *)bias, (float *)h, z_out);
     return hipGetLastError();
 }
 

@@ -54,6 +54,10 @@ struct LayerPlan {           // weight matrix l = 1..t
     size_t off_W = 0, off_b = 0;   // byte offsets into the subnet buffer
     size_t off_act = 0;            // workspace: h_l [S][maxB][R] dtype (l < t), logits fp32 (l == t)
     size_t off_dz = 0;             // workspace: dz_l [S][maxB][R] dtype
+    // with per-neuron standardisation (hidden layers only):
+    size_t off_z = 0;              // workspace: z_l  [S][maxB][ldr] fp32, input of the standardisation
+    size_t off_zh = 0;             // workspace: zh_l [S][maxB][ldr] dtype, standardised value before the ReLU
+    size_t off_isg = 0;            // workspace: 1/sigma [S][ldr] fp32
 };
 
 struct HiddenPlan {          // hidden layer l = 1..t-1
@@ -70,7 +74,8 @@ struct HiddenPlan {          // hidden layer l = 1..t-1
 }  // namespace ist
 
 struct ist_ctx {
-    int32_t t = 0, S = 0, dtype = 0, input = 0, has_bias = 0, max_B = 0;
+    int32_t t = 0, S = 0, dtype = 0, input = 0, has_bias = 0, max_B = 0, normalize = 0;
+    float norm_eps = 1e-5f;
     std::vector<int64_t> dims;
     std::vector<ist::LayerPlan> layer;    // index l-1
     std::vector<ist::HiddenPlan> hidden;  // index l-1, l = 1..t-1
@@ -100,7 +105,7 @@ namespace ist {
 enum KernelClass {
     KC_PERM_TABLES = 0, KC_PARTITION_COPY, KC_MERGE_COPY, KC_BIAS_COPY, KC_GEMM_FWD, KC_GEMM_BWD_DATA,
     KC_GEMM_UPDATE, KC_SOFTMAX_XENT, KC_LOSS_REDUCE, KC_BIAS_UPDATE, KC_CSR_FORWARD, KC_CSR_UPDATE,
-    KC_COUNT
+    KC_NORM, KC_COUNT
 };
 
 // What the last launcher call ran: kernel label (launch configuration), algorithmic flops and
@@ -185,6 +190,14 @@ hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t s
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
                                int64_t ld, int dtype, hipStream_t st);
+// Section 2.2 standardisation of hidden-neuron inputs over the mini-batch, per subnet g and column r:
+// forward: zh = (z - mean_b z) / sqrt(var_b z + eps) -> dtype, h = max(zh, 0), isg = 1 / sigma;
+// backward (in place on dz, which holds dzh = dh * [zh > 0]):
+//   dz = (dzh - mean_b dzh - zh * mean_b(dzh * zh)) * isg.
+hipError_t launch_norm_forward(const float *z, void *zh, void *h, float *isg, int32_t G, int32_t B, int64_t R,
+                               int64_t ld, float eps, int dtype, hipStream_t st);
+hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int32_t G, int32_t B, int64_t R,
+                                int64_t ld, int dtype, hipStream_t st);
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
                               int32_t G, int32_t B, hipStream_t st);
 struct BiasJob { void *bias; const void *dz; int64_t R, ld; int32_t blk0; };
@@ -199,7 +212,8 @@ struct CsrArgs {
     int32_t G, B; int64_t N0, w;
     int64_t ld;               // row pitch of h_1 / dz_1
 };
-hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h,
+// z_out != null: write the fp32 pre-activation there instead of ReLU(.) to h
+hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out,
                               int dtype, hipStream_t st);
 hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_t *bitmap,
                              float lr, int dtype, hipStream_t st);

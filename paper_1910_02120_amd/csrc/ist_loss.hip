@@ -179,6 +179,102 @@ hipError_t launch_lse_combine(const float *pmax, const float *psum, int32_t nb, 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Per-neuron standardisation over the mini-batch (Section 2.2 "Correcting Distributional
+// Shift"; no learned scale or shift, statistics of the current batch, fp32 arithmetic).
+// A workgroup owns 64 columns of one subnet; its 4 wavefronts split the batch rows
+// (row b goes to wave b % 4, ascending), partial sums meet in LDS in fixed order.
+// ---------------------------------------------------------------------------------------
+__device__ inline float col_reduce4(float v, float (*sh)[64], int wave, int lane)
+{
+    __syncthreads();
+    sh[wave][lane] = v;
+    __syncthreads();
+    return (sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane]);
+}
+
+template <typename D>
+__global__ __launch_bounds__(256) void k_norm_forward(const float *__restrict__ z, typename D::T *__restrict__ zh,
+                                                      typename D::T *__restrict__ h, float *__restrict__ isg,
+                                                      int32_t B, int64_t R, int64_t ld, float eps)
+{
+    using T = typename D::T;
+    __shared__ float sh[4][64];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const bool ok = r < R;
+    const int64_t base = (int64_t)g * B * ld + (ok ? r : 0);
+    const float invB = 1.0f / (float)B;
+    float acc = 0.0f;
+    for (int b = wave; b < B; b += 4) acc += ok ? z[base + (int64_t)b * ld] : 0.0f;
+    const float mu = col_reduce4(acc, sh, wave, lane) * invB;
+    acc = 0.0f;
+    for (int b = wave; b < B; b += 4) {
+        const float d = (ok ? z[base + (int64_t)b * ld] : mu) - mu;
+        acc = fmaf(d, d, acc);
+    }
+    const float var = col_reduce4(acc, sh, wave, lane) * invB;
+    const float inv = 1.0f / sqrtf(var + eps);
+    if (!ok) return;
+    if (wave == 0) isg[(int64_t)g * ld + r] = inv;
+    for (int b = wave; b < B; b += 4) {
+        const T v = D::cvt((z[base + (int64_t)b * ld] - mu) * inv);
+        zh[base + (int64_t)b * ld] = v;
+        h[base + (int64_t)b * ld] = D::up(v) > 0.0f ? v : D::cvt(0.0f);
+    }
+}
+
+template <typename D>
+__global__ __launch_bounds__(256) void k_norm_backward(typename D::T *__restrict__ dz,
+                                                       const typename D::T *__restrict__ zh,
+                                                       const float *__restrict__ isg, int32_t B, int64_t R, int64_t ld)
+{
+    __shared__ float sh[4][64];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const bool ok = r < R;
+    const int64_t base = (int64_t)g * B * ld + (ok ? r : 0);
+    const float invB = 1.0f / (float)B;
+    float a1 = 0.0f, a2 = 0.0f;
+    for (int b = wave; b < B; b += 4) {
+        const float d = ok ? D::ld(dz + base + (int64_t)b * ld) : 0.0f;
+        const float v = ok ? D::ld(zh + base + (int64_t)b * ld) : 0.0f;
+        a1 += d;
+        a2 = fmaf(d, v, a2);
+    }
+    const float s1 = col_reduce4(a1, sh, wave, lane) * invB;
+    const float s2 = col_reduce4(a2, sh, wave, lane) * invB;
+    if (!ok) return;
+    const float inv = isg[(int64_t)g * ld + r];
+    for (int b = wave; b < B; b += 4) {
+        const float d = D::ld(dz + base + (int64_t)b * ld);
+        const float v = D::ld(zh + base + (int64_t)b * ld);
+        dz[base + (int64_t)b * ld] = D::cvt((d - s1 - v * s2) * inv);
+    }
+}
+
+hipError_t launch_norm_forward(const float *z, void *zh, void *h, float *isg, int32_t G, int32_t B, int64_t R,
+                               int64_t ld, float eps, int dtype, hipStream_t st)
+{
+    const dim3 grid((unsigned)((R + 63) / 64), (unsigned)G);
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL(k_norm_forward<BF16>, grid, dim3(256), 0, st, z, (uint16_t *)zh, (uint16_t *)h, isg, B, R, ld, eps);
+    else
+        hipLaunchKernelGGL(k_norm_forward<F32>, grid, dim3(256), 0, st, z, (float *)zh, (float *)h, isg, B, R, ld, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int32_t G, int32_t B, int64_t R,
+                                int64_t ld, int dtype, hipStream_t st)
+{
+    const dim3 grid((unsigned)((R + 63) / 64), (unsigned)G);
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL(k_norm_backward<BF16>, grid, dim3(256), 0, st, (uint16_t *)dz, (const uint16_t *)zh, isg, B, R, ld);
+    else
+        hipLaunchKernelGGL(k_norm_backward<F32>, grid, dim3(256), 0, st, (float *)dz, (const float *)zh, isg, B, R, ld);
+    return hipGetLastError();
+}
+
 // b_l[g][r] <- b_l[g][r] - lr * sum_b dz_l[g][b][r] for several layers in one launch.
 // A workgroup owns 64 columns of one (layer, subnet); its 4 wavefronts split the
 // batch rows, partial sums meet in LDS, summation order is fixed.

@@ -64,3 +64,22 @@ def test_create_validates_the_description(lib):
     assert _create(lib, [8, 16, 4], 2, max_B=0)[0] == -2
     assert _create(lib, [8, 0, 4], 1)[0] == -2
     assert lib.ist_create(None, 1, None) == -1
+
+
+def test_create_validates_the_normalisation_fields(lib):
+    from paper_1910_02120_amd.binding import _ModelDesc
+    dims = [8, 16, 16, 4]
+    arr = (C.c_int64 * len(dims))(*dims)
+    sizes = []
+    for norm in (0, 1):
+        ctx = C.c_void_p()
+        d = _ModelDesc(3, arr, 4, 0, 0, 1, norm, 0.0)
+        assert lib.ist_create(C.byref(d), 8, C.byref(ctx)) == 0
+        n = C.c_size_t()
+        assert lib.ist_workspace_bytes(ctx, C.byref(n)) == 0
+        sizes.append(n.value)
+        assert lib.ist_destroy(ctx) == 0
+    assert sizes[1] > sizes[0]            # pre-activations, standardised values, 1/sigma per hidden layer
+    ctx = C.c_void_p()
+    assert lib.ist_create(C.byref(_ModelDesc(3, arr, 4, 0, 0, 1, 2, 0.0)), 8, C.byref(ctx)) == -1
+    assert lib.ist_create(C.byref(_ModelDesc(3, arr, 4, 0, 0, 1, 1, float("nan"))), 8, C.byref(ctx)) == -1

@@ -277,3 +277,21 @@ def test_single_class_and_as_many_subnets_as_neurons(dims, S, B):
     H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, H.TOL[cfg.dtype])
     np.testing.assert_allclose(loss, want_loss, rtol=1e-2, atol=1e-5)
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "big-tiles-bf16",
+                                  "csr-f32", "cfg5-small", "one-hidden-B1-f32", "deep-bf16"])
+def test_k_local_steps_with_standardisation_match_oracle(name):
+    """Section 2.2: every hidden neuron's input standardised over the mini-batch before the ReLU."""
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, dev=_dev(), normalize=True)
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    loss = P.gpu_steps(ctx)
+    subs = P.oracle_subnets()
+    want_loss = P.oracle_steps(subs)
+    tol = H.TOL[cfg.dtype]
+    worst = H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, tol)
+    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
+    print(f"{name} (standardised): worst parameter rel err {worst:.3e} (tol {tol})")
+    ctx.close()
