@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--normalize", action="store_true",
+                    help="standardise hidden-neuron inputs over the mini-batch (Section 2.2 of the paper); "
+                         "off for the headline metric")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain device copy of 1 GiB three times (reference dispatch for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -192,7 +195,8 @@ def main():
         del src, dst
     nd = min(cfg.rounds, 4) if cfg.idx <= 3 else 1
     dW, db, perms, data = device_problem(cfg, nd, dev)
-    ctx = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B, device="cuda:0")
+    ctx = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B, device="cuda:0",
+                     normalize=args.normalize)
     loss = torch.zeros(cfg.S * cfg.k, dtype=torch.float32, device=dev)
 
     for i in range(args.warmup):
@@ -277,7 +281,7 @@ def main():
         "ms_per_step": ms_round, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "dims": list(cfg.dims), "S": cfg.S, "B": cfg.B, "k": cfg.k,
-                   "lr": cfg.lr, "input": cfg.input, "step": "one IST round: partition + k local SGD steps on S subnets + merge"},
+                   "lr": cfg.lr, "input": cfg.input, "normalize": bool(args.normalize), "step": "one IST round: partition + k local SGD steps on S subnets + merge"},
         "phases": {
             "partition_ms": phase[0], "steps_ms": phase[1], "merge_ms": phase[2],
             "steps_samples_per_s": samples_round / (phase[1] * 1e-3),

@@ -253,10 +253,117 @@ __global__ __launch_bounds__(256) void k_norm_backward(typename D::T *__restrict
     }
 }
 
+// Batches of up to 512 rows: 16 wavefronts per workgroup, every thread keeps its (at most 32) rows of
+// the column in registers, so the pre-activations are read once and all loads are in flight together.
+constexpr int kNormWaves = 16, kNormRows = 32;
+
+__device__ inline float col_reduce16(float v, float (*sh)[64], int wave, int lane)
+{
+    __syncthreads();
+    sh[wave][lane] = v;
+    __syncthreads();
+    float t[kNormWaves];
+#pragma unroll
+    for (int i = 0; i < kNormWaves; ++i) t[i] = sh[i][lane];
+#pragma unroll
+    for (int d = 1; d < kNormWaves; d *= 2)
+#pragma unroll
+        for (int i = 0; i + d < kNormWaves; i += 2 * d) t[i] += t[i + d];
+    return t[0];
+}
+
+template <typename D>
+__global__ __launch_bounds__(64 * kNormWaves) void k_norm_forward_reg(const float *__restrict__ z,
+                                                                      typename D::T *__restrict__ zh,
+                                                                      typename D::T *__restrict__ h,
+                                                                      float *__restrict__ isg, int32_t B, int64_t R,
+                                                                      int64_t ld, float eps)
+{
+    using T = typename D::T;
+    __shared__ float sh[kNormWaves][64];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const bool ok = r < R;
+    const int64_t base = (int64_t)g * B * ld + (ok ? r : 0);
+    const float invB = 1.0f / (float)B;
+    float v[kNormRows];
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        v[i] = (ok && b < B) ? z[base + (int64_t)b * ld] : 0.0f;
+    }
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) acc += v[i];
+    const float mu = col_reduce16(acc, sh, wave, lane) * invB;
+    acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const float d = (wave + kNormWaves * i < B) ? v[i] - mu : 0.0f;
+        acc = fmaf(d, d, acc);
+    }
+    const float var = col_reduce16(acc, sh, wave, lane) * invB;
+    const float inv = 1.0f / sqrtf(var + eps);
+    if (!ok) return;
+    if (wave == 0) isg[(int64_t)g * ld + r] = inv;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        if (b < B) {
+            const T q = D::cvt((v[i] - mu) * inv);
+            zh[base + (int64_t)b * ld] = q;
+            h[base + (int64_t)b * ld] = D::up(q) > 0.0f ? q : D::cvt(0.0f);
+        }
+    }
+}
+
+template <typename D>
+__global__ __launch_bounds__(64 * kNormWaves) void k_norm_backward_reg(typename D::T *__restrict__ dz,
+                                                                       const typename D::T *__restrict__ zh,
+                                                                       const float *__restrict__ isg, int32_t B,
+                                                                       int64_t R, int64_t ld)
+{
+    __shared__ float sh[kNormWaves][64];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    const bool ok = r < R;
+    const int64_t base = (int64_t)g * B * ld + (ok ? r : 0);
+    const float invB = 1.0f / (float)B;
+    float d[kNormRows], v[kNormRows];
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        const bool in = ok && b < B;
+        d[i] = in ? D::ld(dz + base + (int64_t)b * ld) : 0.0f;
+        v[i] = in ? D::ld(zh + base + (int64_t)b * ld) : 0.0f;
+    }
+    float a1 = 0.0f, a2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) { a1 += d[i]; a2 = fmaf(d[i], v[i], a2); }
+    const float s1 = col_reduce16(a1, sh, wave, lane) * invB;
+    const float s2 = col_reduce16(a2, sh, wave, lane) * invB;
+    if (!ok) return;
+    const float inv = isg[(int64_t)g * ld + r];
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        if (b < B) dz[base + (int64_t)b * ld] = D::cvt((d[i] - s1 - v[i] * s2) * inv);
+    }
+}
+
 hipError_t launch_norm_forward(const float *z, void *zh, void *h, float *isg, int32_t G, int32_t B, int64_t R,
                                int64_t ld, float eps, int dtype, hipStream_t st)
 {
     const dim3 grid((unsigned)((R + 63) / 64), (unsigned)G);
+    if (B <= kNormWaves * kNormRows) {
+        if (dtype == IST_BF16)
+            hipLaunchKernelGGL(k_norm_forward_reg<BF16>, grid, dim3(64 * kNormWaves), 0, st, z, (uint16_t *)zh, (uint16_t *)h,
+                               isg, B, R, ld, eps);
+        else
+            hipLaunchKernelGGL(k_norm_forward_reg<F32>, grid, dim3(64 * kNormWaves), 0, st, z, (float *)zh, (float *)h, isg, B,
+                               R, ld, eps);
+        return hipGetLastError();
+    }
     if (dtype == IST_BF16)
         hipLaunchKernelGGL(k_norm_forward<BF16>, grid, dim3(256), 0, st, z, (uint16_t *)zh, (uint16_t *)h, isg, B, R, ld, eps);
     else
@@ -268,6 +375,15 @@ hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int3
                                 int64_t ld, int dtype, hipStream_t st)
 {
     const dim3 grid((unsigned)((R + 63) / 64), (unsigned)G);
+    if (B <= kNormWaves * kNormRows) {
+        if (dtype == IST_BF16)
+            hipLaunchKernelGGL(k_norm_backward_reg<BF16>, grid, dim3(64 * kNormWaves), 0, st, (uint16_t *)dz,
+                               (const uint16_t *)zh, isg, B, R, ld);
+        else
+            hipLaunchKernelGGL(k_norm_backward_reg<F32>, grid, dim3(64 * kNormWaves), 0, st, (float *)dz, (const float *)zh,
+                               isg, B, R, ld);
+        return hipGetLastError();
+    }
     if (dtype == IST_BF16)
         hipLaunchKernelGGL(k_norm_backward<BF16>, grid, dim3(256), 0, st, (uint16_t *)dz, (const uint16_t *)zh, isg, B, R, ld);
     else

@@ -19,10 +19,10 @@ pytestmark = pytest.mark.gpu
 C = gen.CONFIGS
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
-def test_full_round_matches_oracle(name):
+@pytest.mark.parametrize("name,normalize", [("cfg2", False), ("cfg3", False), ("cfg2", True), ("cfg3", True)])
+def test_full_round_matches_oracle(name, normalize):
     cfg = C[name]
-    P = H.Problem(cfg, bias_scale=0.02)
+    P = H.Problem(cfg, bias_scale=0.02, normalize=normalize)
     ctx = P.context()
     ctx.set_checked(True)
     ctx.partition(P.dW, P.db, P.dperm)
@@ -102,8 +102,8 @@ def _sampled_partition_check(cfg, ctx, dW, db, perms, rng, n_rows=6):
             assert np.array_equal(H.bits(bsub)[pick], wb), (l, s, "bias")
 
 
-@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
-def test_large_workload_sampled_parity(name):
+@pytest.mark.parametrize("name,normalize", [("cfg4", False), ("cfg5", False), ("cfg4", True), ("cfg5", True)])
+def test_large_workload_sampled_parity(name, normalize):
     cfg = C[name]
     dev = torch.device("cuda:0")
     g = torch.Generator(device=dev)
@@ -113,7 +113,7 @@ def test_large_workload_sampled_parity(name):
     perms = gen.make_perms(cfg)
     dperm = [torch.from_numpy(p).to(dev) for p in perms]
     from paper_1910_02120_amd import ISTContext
-    ctx = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B)
+    ctx = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B, normalize=normalize)
     ctx.partition(dW, db, dperm)
     _sampled_partition_check(cfg, ctx, dW, db, perms, rng)
 
@@ -162,10 +162,10 @@ def test_large_workload_sampled_parity(name):
     ctx.subnet_steps(dy, lr, 1, cfg.B, X=dX, csr=dcsr, loss_out=lo)
     torch.cuda.synchronize()
     if cfg.input == "csr":
-        want_loss = orc.subnet_sgd(Wl, bl, y[s0], lr, 1, cfg.dtype,
+        want_loss = orc.subnet_sgd(Wl, bl, y[s0], lr, 1, cfg.dtype, normalize=normalize,
                                    csr=orc.csr_slice(rp, ci, va.astype(np.float64), s0 * cfg.B, (s0 + 1) * cfg.B))
     else:
-        want_loss = orc.subnet_sgd(Wl, bl, y[s0], lr, 1, cfg.dtype, X=X[s0].astype(np.float64))
+        want_loss = orc.subnet_sgd(Wl, bl, y[s0], lr, 1, cfg.dtype, X=X[s0].astype(np.float64), normalize=normalize)
     # the oracle worked in H^s order; export gives the same order
     tol = H.TOL[cfg.dtype]
     worst = 0.0
