@@ -351,10 +351,112 @@ __global__ __launch_bounds__(64 * kNormWaves) void k_norm_backward_reg(typename 
     }
 }
 
+// bf16 layers at least 2048 wide: two neighbouring columns per lane (8-byte loads of z, 4-byte packed
+// accesses of the bf16 arrays), 128 columns per workgroup.  Needs an even pitch (it is a multiple of 8).
+__global__ __launch_bounds__(64 * kNormWaves) void k_norm_forward_bf16x2(const float *__restrict__ z,
+                                                                         uint32_t *__restrict__ zh,
+                                                                         uint32_t *__restrict__ h,
+                                                                         float *__restrict__ isg, int32_t B, int64_t R,
+                                                                         int64_t ld, float eps)
+{
+    __shared__ float sh[kNormWaves][64];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = ((int64_t)blockIdx.x * 64 + lane) * 2;   // r even, ld even: r + 1 < ld whenever r < R
+    const bool ok = r < R;
+    const int64_t base = (int64_t)g * B * ld + (ok ? r : 0);
+    const float invB = 1.0f / (float)B;
+    float2 v[kNormRows];
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        v[i] = (ok && b < B) ? *reinterpret_cast<const float2 *>(z + base + (int64_t)b * ld) : float2{0.0f, 0.0f};
+    }
+    float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) { a0 += v[i].x; a1 += v[i].y; }
+    const float mu0 = col_reduce16(a0, sh, wave, lane) * invB;
+    const float mu1 = col_reduce16(a1, sh, wave, lane) * invB;
+    a0 = a1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const bool in = wave + kNormWaves * i < B;
+        const float d0 = in ? v[i].x - mu0 : 0.0f, d1 = in ? v[i].y - mu1 : 0.0f;
+        a0 = fmaf(d0, d0, a0);
+        a1 = fmaf(d1, d1, a1);
+    }
+    const float inv0 = 1.0f / sqrtf(col_reduce16(a0, sh, wave, lane) * invB + eps);
+    const float inv1 = 1.0f / sqrtf(col_reduce16(a1, sh, wave, lane) * invB + eps);
+    if (!ok) return;
+    if (wave == 0) { isg[(int64_t)g * ld + r] = inv0; isg[(int64_t)g * ld + r + 1] = inv1; }
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        if (b < B) {
+            const uint32_t q = f32x2_to_bf16x2((v[i].x - mu0) * inv0, (v[i].y - mu1) * inv1);
+            const uint32_t lo = (q & 0x8000u) || !(q & 0x7fffu) ? 0u : (q & 0xffffu);          // max(. , 0) per half
+            const uint32_t hi = (q & 0x80000000u) || !(q & 0x7fff0000u) ? 0u : (q & 0xffff0000u);
+            zh[(base + (int64_t)b * ld) >> 1] = q;
+            h[(base + (int64_t)b * ld) >> 1] = lo | hi;
+        }
+    }
+}
+
+__global__ __launch_bounds__(64 * kNormWaves) void k_norm_backward_bf16x2(uint32_t *__restrict__ dz,
+                                                                          const uint32_t *__restrict__ zh,
+                                                                          const float *__restrict__ isg, int32_t B,
+                                                                          int64_t R, int64_t ld)
+{
+    __shared__ float sh[kNormWaves][64];
+    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = ((int64_t)blockIdx.x * 64 + lane) * 2;
+    const bool ok = r < R;
+    const int64_t base = (int64_t)g * B * ld + (ok ? r : 0);
+    const float invB = 1.0f / (float)B;
+    uint32_t d[kNormRows], v[kNormRows];
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        const bool in = ok && b < B;
+        d[i] = in ? dz[(base + (int64_t)b * ld) >> 1] : 0u;
+        v[i] = in ? zh[(base + (int64_t)b * ld) >> 1] : 0u;
+    }
+    auto lo = [](uint32_t x) { return __uint_as_float(x << 16); };
+    auto hi = [](uint32_t x) { return __uint_as_float(x & 0xffff0000u); };
+    float p0 = 0.0f, p1 = 0.0f, q0 = 0.0f, q1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        p0 += lo(d[i]); p1 += hi(d[i]);
+        q0 = fmaf(lo(d[i]), lo(v[i]), q0);
+        q1 = fmaf(hi(d[i]), hi(v[i]), q1);
+    }
+    const float s10 = col_reduce16(p0, sh, wave, lane) * invB, s11 = col_reduce16(p1, sh, wave, lane) * invB;
+    const float s20 = col_reduce16(q0, sh, wave, lane) * invB, s21 = col_reduce16(q1, sh, wave, lane) * invB;
+    if (!ok) return;
+    const float inv0 = isg[(int64_t)g * ld + r], inv1 = isg[(int64_t)g * ld + r + 1];
+#pragma unroll
+    for (int i = 0; i < kNormRows; ++i) {
+        const int b = wave + kNormWaves * i;
+        if (b < B)
+            dz[(base + (int64_t)b * ld) >> 1] = f32x2_to_bf16x2((lo(d[i]) - s10 - lo(v[i]) * s20) * inv0,
+                                                                (hi(d[i]) - s11 - hi(v[i]) * s21) * inv1);
+    }
+}
+
+static bool norm_pairs_ok(const void *a, const void *b, int64_t R, int64_t ld, int32_t B, int dtype)
+{
+    return dtype == IST_BF16 && R >= 2048 && ld % 2 == 0 && ((int64_t)B * ld) % 2 == 0 &&
+           reinterpret_cast<uintptr_t>(a) % 8 == 0 && reinterpret_cast<uintptr_t>(b) % 8 == 0;
+}
+
 hipError_t launch_norm_forward(const float *z, void *zh, void *h, float *isg, int32_t G, int32_t B, int64_t R,
                                int64_t ld, float eps, int dtype, hipStream_t st)
 {
     const dim3 grid((unsigned)((R + 63) / 64), (unsigned)G);
+    if (B <= kNormWaves * kNormRows && norm_pairs_ok(z, zh, R, ld, B, dtype) && reinterpret_cast<uintptr_t>(h) % 8 == 0) {
+        hipLaunchKernelGGL(k_norm_forward_bf16x2, dim3((unsigned)((R + 127) / 128), (unsigned)G), dim3(64 * kNormWaves), 0, st,
+                           z, (uint32_t *)zh, (uint32_t *)h, isg, B, R, ld, eps);
+        return hipGetLastError();
+    }
     if (B <= kNormWaves * kNormRows) {
         if (dtype == IST_BF16)
             hipLaunchKernelGGL(k_norm_forward_reg<BF16>, grid, dim3(64 * kNormWaves), 0, st, z, (uint16_t *)zh, (uint16_t *)h,
@@ -375,6 +477,11 @@ hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int3
                                 int64_t ld, int dtype, hipStream_t st)
 {
     const dim3 grid((unsigned)((R + 63) / 64), (unsigned)G);
+    if (B <= kNormWaves * kNormRows && norm_pairs_ok(dz, zh, R, ld, B, dtype)) {
+        hipLaunchKernelGGL(k_norm_backward_bf16x2, dim3((unsigned)((R + 127) / 128), (unsigned)G), dim3(64 * kNormWaves), 0, st,
+                           (uint32_t *)dz, (const uint32_t *)zh, isg, B, R, ld);
+        return hipGetLastError();
+    }
     if (B <= kNormWaves * kNormRows) {
         if (dtype == IST_BF16)
             hipLaunchKernelGGL(k_norm_backward_reg<BF16>, grid, dim3(64 * kNormWaves), 0, st, (uint16_t *)dz,
