@@ -171,6 +171,112 @@ __global__ __launch_bounds__(256) void k_rows_transposed(E *__restrict__ W, int6
     }
 }
 
+// The same for 2-byte elements with wider accesses: a tile of 64 rows x 128 columns; the packed
+// side moves 16 bytes per lane (8 consecutive q of one column), the full matrix 4 bytes per lane.
+// A row of W starts at an arbitrary element (odd row lengths), so a row's aligned 4-byte words are
+// staged in LDS with the row's one-element misalignment kept, and the transposing side reads
+// column c of row q at position mis_q + c.  Words that straddle the tile's column range are
+// written element by element on merge (their other half belongs to a neighbour).
+constexpr int kTrQ = 64, kTrC = 128;
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void k_rows_transposed16(uint16_t *__restrict__ W, int64_t ld,
+                                                           uint16_t *__restrict__ sub, const int32_t *__restrict__ rows,
+                                                           int64_t nr, int64_t nc)
+{
+    __shared__ uint32_t tile[kTrQ][kTrC / 2 + 2];
+    __shared__ int64_t start[kTrQ];                         // element index of (row, c0) in W
+    const int g = blockIdx.z;
+    const int64_t q0 = (int64_t)blockIdx.y * kTrQ, c0 = (int64_t)blockIdx.x * kTrC;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    uint16_t *pack = sub + (int64_t)g * nr * nc;            // [nc][nr]
+    uint32_t *W32 = reinterpret_cast<uint32_t *>(W);
+    if (threadIdx.x < kTrQ) {
+        const int64_t q = q0 + threadIdx.x;
+        start[threadIdx.x] = q < nr ? (int64_t)rows[g * nr + q] * ld + c0 : -1;
+    }
+    __syncthreads();
+    const int64_t ncol = nc - c0 < kTrC ? nc - c0 : kTrC;   // valid columns of this tile
+    // ---- packed side <-> LDS: thread (crow, lq) owns 8 consecutive q of one column ----
+    auto packed_side = [&]() {
+        const int lq = threadIdx.x & 7;
+#pragma unroll
+        for (int pass = 0; pass < kTrC / 32; ++pass) {
+            const int crow = (threadIdx.x >> 3) + 32 * pass;
+            if (crow >= ncol) continue;
+            uint16_t *dst = pack + (c0 + crow) * nr + q0 + lq * 8;
+            const bool full = q0 + lq * 8 + 8 <= nr;
+            if (SCATTER) {
+                uint16_t v[8];
+                if (full) __builtin_memcpy(v, __builtin_assume_aligned(dst, 16), 16);
+                else
+                    for (int j = 0; j < 8; ++j) v[j] = q0 + lq * 8 + j < nr ? dst[j] : (uint16_t)0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int qi = lq * 8 + j;
+                    reinterpret_cast<uint16_t *>(tile[qi])[(start[qi] & 1) + crow] = v[j];
+                }
+            } else {
+                uint16_t v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int qi = lq * 8 + j;
+                    v[j] = reinterpret_cast<const uint16_t *>(tile[qi])[(start[qi] & 1) + crow];
+                }
+                if (full) __builtin_memcpy(__builtin_assume_aligned(dst, 16), v, 16);
+                else
+                    for (int j = 0; j < 8; ++j)
+                        if (q0 + lq * 8 + j < nr) dst[j] = v[j];
+            }
+        }
+    };
+    if (SCATTER) { packed_side(); __syncthreads(); }
+    if (!SCATTER) {
+        // all 16 row passes' words are requested before any is stored to LDS; a word outside the
+        // tile's columns is read from word 0 of W instead (no branch around the loads)
+        uint32_t v[kTrQ / 4];
+#pragma unroll
+        for (int pass = 0; pass < kTrQ / 4; ++pass) {
+            const int64_t e0 = start[pass * 4 + ty];
+            const int mis = (int)(e0 & 1);
+            const int64_t lo = 2 * tx - mis;
+            const int64_t e = e0 + lo;                      // first element of the word
+            const bool ok = e0 >= 0 && lo < ncol;           // the row count is a multiple of 8, so W holds an
+            v[pass] = W32[ok ? (e >> 1) : 0];               // even number of elements and ends on a word
+        }
+#pragma unroll
+        for (int pass = 0; pass < kTrQ / 4; ++pass) tile[pass * 4 + ty][tx] = v[pass];
+        // the 65th word of a misaligned row
+        for (int i = threadIdx.x; i < kTrQ; i += 256) {
+            const int64_t e0 = start[i];
+            if (e0 >= 0 && (e0 & 1) && kTrC - 1 < ncol) tile[i][kTrC / 2] = W32[(e0 + kTrC - 1) >> 1];
+        }
+        __syncthreads();
+        packed_side();
+        return;
+    }
+    // ---- merge: LDS -> full matrix, 4 rows per pass, one aligned word per lane (+1 spill word) ----
+#pragma unroll
+    for (int pass = 0; pass < kTrQ / 4; ++pass) {
+        const int qi = pass * 4 + ty;
+        const int64_t e0 = start[qi];
+        if (e0 < 0) continue;
+        const int mis = (int)(e0 & 1);
+        const int64_t w0 = (e0 - mis) >> 1;                 // first word of the staged range
+        for (int k = tx; k < kTrC / 2 + 1; k += 64) {       // second trip: only lane 0 (word 64)
+            const int64_t lo = 2 * k - mis, hi = lo + 1;    // tile columns held by word k
+            if (hi < 0 || lo >= ncol) continue;
+            const bool whole = lo >= 0 && hi < ncol;
+            if (whole) {
+                W32[w0 + k] = tile[qi][k];
+            } else {
+                const uint16_t *t16 = reinterpret_cast<const uint16_t *>(tile[qi]);
+                if (lo >= 0 && lo < ncol) W[e0 + lo] = t16[2 * k];
+                if (hi >= 0 && hi < ncol) W[e0 + hi] = t16[2 * k + 1];
+            }
+        }
+    }
+}
+
 // ----------------------------------------------------------------------------
 // column-partitioned blocks (middle and last layers)
 // ----------------------------------------------------------------------------
@@ -337,6 +443,13 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
                                   : (SCATTER && a.rows ? 2.0 * rows_b + sub_b : rows_b + sub_b);
     if (a.transposed) {
         tag_kernel(SCATTER ? "k_rows_transposed<scatter>" : "k_rows_transposed<gather>", 0.0, line_b);
+        if (sizeof(E) == 2 && reinterpret_cast<uintptr_t>(W) % 4 == 0 && reinterpret_cast<uintptr_t>(sub) % 16 == 0 &&
+            a.nr % 8 == 0 && ((int64_t)a.nr * a.nc) % 8 == 0 && a.G * a.nr == a.N_out) {
+            dim3 grid((unsigned)((a.nc + kTrC - 1) / kTrC), (unsigned)((a.nr + kTrQ - 1) / kTrQ), (unsigned)a.G);
+            hipLaunchKernelGGL((k_rows_transposed16<SCATTER>), grid, dim3(256), 0, st, reinterpret_cast<uint16_t *>(W), a.ld,
+                               reinterpret_cast<uint16_t *>(sub), a.rows, a.nr, a.nc);
+            return hipGetLastError();
+        }
         dim3 grid((unsigned)((a.nc + 63) / 64), (unsigned)((a.nr + 63) / 64), (unsigned)a.G);
         hipLaunchKernelGGL((k_rows_transposed<E, SCATTER>), grid, dim3(256), 0, st, W, a.ld, sub,
                            a.rows, a.nr, a.nc);

@@ -40,6 +40,10 @@ SHAPES = {
     "one-hidden-B1-f32": _mk("one-hidden-B1-f32", "cfg2", dims=(40, 64, 7), S=4, B=1, k=2, lr=0.05),
     "deep-bf16": _mk("deep-bf16", "cfg3", dims=(64, 128, 256, 128, 64, 12), S=4, B=20, k=3, lr=0.05),
     "width-one-blocks-f32": _mk("width-one-blocks-f32", "cfg2", dims=(24, 8, 8, 5), S=8, B=9, k=2, lr=0.05),
+    # sparse first layer in bf16 (transposed storage): even row length with 128 rows per subnet, and
+    # an odd row length with 8 rows per subnet
+    "csr-bf16-even": _mk("csr-bf16-even", "cfg5", dims=(1000, 512, 77), S=4, B=21, k=2, nnz_per_row=12, lr=0.5),
+    "csr-bf16-odd": _mk("csr-bf16-odd", "cfg5", dims=(777, 64, 50), S=8, B=10, k=2, nnz_per_row=7, lr=0.5),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
