@@ -62,6 +62,10 @@ CONFIGS = {
                       k=10, rounds=1, dtype="bf16"),
     "cfg5": ISTConfig("cfg5-extreme-classification", 5, (135909, 1024, 670091), S=8, B=256,
                       k=5, rounds=1, dtype="bf16", input="csr", label_dist="zipf"),
+    # beyond the five benchmark configurations: the paper's larger speech model (Section 3.1: three
+    # hidden layers of 8192 neurons, 4096-dimensional features, 35 keywords); S, B, k are ours
+    "speech8192": ISTConfig("speech-3x8192", 6, (4096, 8192, 8192, 8192, 35), S=8, B=128, k=10,
+                            rounds=4, dtype="f32"),
 }
 
 

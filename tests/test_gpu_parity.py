@@ -44,6 +44,7 @@ SHAPES = {
     # an odd row length with 8 rows per subnet
     "csr-bf16-even": _mk("csr-bf16-even", "cfg5", dims=(1000, 512, 77), S=4, B=21, k=2, nnz_per_row=12, lr=0.5),
     "csr-bf16-odd": _mk("csr-bf16-odd", "cfg5", dims=(777, 64, 50), S=8, B=10, k=2, nnz_per_row=7, lr=0.5),
+    "speech-small": _mk("speech-small", "speech8192", dims=(256, 512, 512, 512, 35), k=3, lr=0.05),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
