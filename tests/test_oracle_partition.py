@@ -91,7 +91,8 @@ def test_parameter_counts_match_closed_form():
     assert full / S ** 2 <= closed <= full / S
     # the benchmark table: parameters per subnet of the five workloads
     want = {"cfg1": 8832, "cfg2": 2132992, "cfg3": 4204544, "cfg4": 168591360, "cfg5": 103168000}
-    for name, c in gen.CONFIGS.items():
+    for name in want:
+        c = gen.CONFIGS[name]
         d, S_ = c.dims, c.S
         p = d[0] * d[1] // S_ + sum(d[i - 1] * d[i] // S_ ** 2 for i in range(2, c.t)) \
             + d[c.t - 1] * d[c.t] // S_
