@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-profile-pass", action="store_true")
+    ap.add_argument("--resample", action="store_true",
+                    help="steady-state rounds: k local steps, then ist_resample (merge + partition by the next "
+                         "permutation in one pass) instead of separate merge and partition calls")
     ap.add_argument("--normalize", action="store_true",
                     help="standardise hidden-neuron inputs over the mini-batch (Section 2.2 of the paper); "
                          "off for the headline metric")
@@ -133,7 +136,14 @@ def work_model(cfg: gen.ISTConfig):
                 useful_copy_bytes=useful, flops_round=fwd + bwd + upd)
 
 
+RESAMPLE = False
+
+
 def run_round(ctx, cfg, dW, db, perms, d, loss=None):
+    if RESAMPLE:   # the subnets of this round were made by the previous round's re-sampling
+        ctx.subnet_steps(d["y"], cfg.lr, cfg.k, cfg.B, X=d["X"], csr=d["csr"], loss_out=loss)
+        ctx.resample(dW, db, perms)
+        return
     ctx.partition(dW, db, perms)
     ctx.subnet_steps(d["y"], cfg.lr, cfg.k, cfg.B, X=d["X"], csr=d["csr"], loss_out=loss)
     ctx.merge(dW, db)
@@ -198,6 +208,10 @@ def main():
     ctx = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B, device="cuda:0",
                      normalize=args.normalize)
     loss = torch.zeros(cfg.S * cfg.k, dtype=torch.float32, device=dev)
+    global RESAMPLE
+    RESAMPLE = args.resample
+    if RESAMPLE:
+        ctx.partition(dW, db, perms[0])
 
     for i in range(args.warmup):
         run_round(ctx, cfg, dW, db, perms[i % nd], data[i % nd], loss)
@@ -223,9 +237,14 @@ def main():
     reps = max(3, min(args.steps, 10))
     for i in range(reps):
         d = data[i % nd]
-        ev[0].record(st); ctx.partition(dW, db, perms[i % nd])
-        ev[1].record(st); ctx.subnet_steps(d["y"], cfg.lr, cfg.k, cfg.B, X=d["X"], csr=d["csr"])
-        ev[2].record(st); ctx.merge(dW, db)
+        if RESAMPLE:   # phases: (nothing), steps, re-sampling
+            ev[0].record(st)
+            ev[1].record(st); ctx.subnet_steps(d["y"], cfg.lr, cfg.k, cfg.B, X=d["X"], csr=d["csr"])
+            ev[2].record(st); ctx.resample(dW, db, perms[i % nd])
+        else:
+            ev[0].record(st); ctx.partition(dW, db, perms[i % nd])
+            ev[1].record(st); ctx.subnet_steps(d["y"], cfg.lr, cfg.k, cfg.B, X=d["X"], csr=d["csr"])
+            ev[2].record(st); ctx.merge(dW, db)
         ev[3].record(st); torch.cuda.synchronize()
         phase += [ev[j].elapsed_time(ev[j + 1]) for j in range(3)]
     phase /= reps
@@ -281,7 +300,7 @@ def main():
         "ms_per_step": ms_round, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "dims": list(cfg.dims), "S": cfg.S, "B": cfg.B, "k": cfg.k,
-                   "lr": cfg.lr, "input": cfg.input, "normalize": bool(args.normalize), "step": "one IST round: partition + k local SGD steps on S subnets + merge"},
+                   "lr": cfg.lr, "input": cfg.input, "normalize": bool(args.normalize), "resample": bool(args.resample), "step": "one IST round: partition + k local SGD steps on S subnets + merge"},
         "phases": {
             "partition_ms": phase[0], "steps_ms": phase[1], "merge_ms": phase[2],
             "steps_samples_per_s": samples_round / (phase[1] * 1e-3),
@@ -292,6 +311,7 @@ def main():
             "partition_GBs_useful": wm["useful_copy_bytes"] / (phase[0] * 1e-3) / 1e9,
             "merge_GBs_useful": wm["useful_copy_bytes"] / (phase[2] * 1e-3) / 1e9,
         },
+        "resample_ms": (phase[2] if RESAMPLE else None),
         "kernel_classes": classes,
         "kernels": kernels[:8],
         "event_overhead_us": EVENT_OVERHEAD_US,

@@ -142,6 +142,21 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *batch, float lr, int3
  */
 ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream);
 
+/*
+ * Re-sampling between rounds (Section 2.1: subnets are re-sampled after every J local
+ * iterations): exactly ist_merge(ctx, params) followed by ist_partition(ctx, params, perm)
+ * - `params` ends up holding the merged network and the context the subnets of the new
+ * permutation, bit for bit - but in one pass over each weight matrix: the row that merge
+ * writes is the row partition would read back.  The new blocks are built in a second
+ * subnet buffer given once with ist_bind_spare (same size and alignment as `subnets` of
+ * ist_bind, caller-owned device memory, must stay valid while the context is used); the
+ * two buffers change roles at every call.  IST_ESTATE before ist_partition or without a
+ * spare buffer; with checking on, a perm that is not a permutation gives IST_EPERM and
+ * leaves `params` and the current subnets untouched.
+ */
+ist_status ist_bind_spare(ist_ctx *ctx, void *spare_subnets, size_t spare_bytes);
+ist_status ist_resample(ist_ctx *ctx, const ist_params *params, const int32_t *const *perm, void *stream);
+
 /* Canonical view of one subnet's layer l (1..t) for inspection and tests:
  * dstW [device] row-major [rows][cols] with rows/cols in the order of the
  * permutation block (H_l^s order), dstb [device] [rows] or NULL. */

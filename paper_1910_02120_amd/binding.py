@@ -25,7 +25,7 @@ EXPORTS = ["ist_create", "ist_destroy", "ist_subnets_bytes", "ist_workspace_byte
            "ist_set_checked", "ist_partition", "ist_subnet_steps", "ist_merge", "ist_subnet_export",
            "ist_subnet_shape", "ist_last_error", "ist_version", "ist_profile_enable",
            "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name",
-           "ist_profile_kernel_count", "ist_profile_kernel"]
+           "ist_profile_kernel_count", "ist_profile_kernel", "ist_bind_spare", "ist_resample"]
 
 
 class ISTError(RuntimeError):
@@ -72,6 +72,8 @@ def load_library() -> C.CDLL:
     lib.ist_partition.argtypes = [p, C.POINTER(_Params), C.POINTER(p), p]
     lib.ist_subnet_steps.argtypes = [p, C.POINTER(_Batch), C.c_float, C.c_int32, p, p]
     lib.ist_merge.argtypes = [p, C.POINTER(_Params), p]
+    lib.ist_bind_spare.argtypes = [p, p, C.c_size_t]
+    lib.ist_resample.argtypes = [p, C.POINTER(_Params), C.POINTER(p), p]
     lib.ist_subnet_export.argtypes = [p, C.c_int32, C.c_int32, p, p, p]
     lib.ist_subnet_shape.argtypes = [p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.ist_profile_enable.argtypes = [p, C.c_int32]
@@ -215,6 +217,19 @@ class ISTContext:
     def merge(self, Ws, bs, stream=None):
         pr = self._params(Ws, bs)
         self._check(self.lib.ist_merge(self._ctx, C.byref(pr), _stream_ptr(stream)))
+
+    def resample(self, Ws, bs, perms: List[torch.Tensor], stream=None):
+        """merge(Ws, bs) followed by partition(Ws, bs, perms), in one pass over the weights.
+        The second subnet buffer it needs is allocated at the first call."""
+        if getattr(self, "spare", None) is None:
+            self.spare = torch.empty(self.subnets_bytes(), dtype=torch.uint8, device=self.device)
+            self._check(self.lib.ist_bind_spare(self._ctx, self.spare.data_ptr(), self.spare.numel()))
+        assert len(perms) == self.t - 1
+        for l, p in enumerate(perms, 1):
+            assert p.is_cuda and p.dtype == torch.int32 and p.is_contiguous() and p.numel() == self.dims[l]
+        pp = (C.c_void_p * max(1, self.t - 1))(*[p.data_ptr() for p in perms])
+        pr = self._params(Ws, bs)
+        self._check(self.lib.ist_resample(self._ctx, C.byref(pr), pp, _stream_ptr(stream)))
 
     # -- inspection ---------------------------------------------------------
     def subnet_shape(self, l: int):

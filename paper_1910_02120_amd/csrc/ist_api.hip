@@ -47,7 +47,7 @@ namespace {
 
 const char *kClassNames[KC_COUNT] = {
     "perm_tables", "partition_copy", "merge_copy", "bias_copy", "gemm_forward", "gemm_backward_data",
-    "gemm_update", "softmax_xent", "loss_reduce", "bias_update", "csr_forward", "csr_update", "norm"};
+    "gemm_update", "softmax_xent", "loss_reduce", "bias_update", "csr_forward", "csr_update", "norm", "resample_copy"};
 
 hipEvent_t prof_event(ist_ctx *ctx)
 {
@@ -97,25 +97,25 @@ inline void set_split(const ist_ctx *ctx, GemmArgs &a)
     a.zeros = ctx->workspace + ctx->off_zeros;
 }
 
-inline const int32_t *tbl(const ist_ctx *ctx, size_t off)
+inline const int32_t *tbl(const char *base, size_t off)
 {
-    return reinterpret_cast<const int32_t *>(ctx->subnets + off);
+    return reinterpret_cast<const int32_t *>(base + off);
 }
 
-// Arguments of the block copy of layer l (1-based) between `params` and the subnet buffer.
-CopyArgs copy_args(const ist_ctx *ctx, int l, void *Wfull)
+// Arguments of the block copy of layer l (1-based) between `params` and a subnet buffer.
+CopyArgs copy_args(const ist_ctx *ctx, char *base, int l, void *Wfull)
 {
     const LayerPlan &L = ctx->layer[l - 1];
     CopyArgs a{};
     a.W = Wfull;
     a.ld = L.N_in;
-    a.sub = ctx->subnets + L.off_W;
-    a.rows = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_sorted) : nullptr;
-    a.cols = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_sorted) : nullptr;
-    a.slotr = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_slot) : nullptr;
-    a.slotc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_slot) : nullptr;
-    a.maskc = L.col_part ? reinterpret_cast<const uint32_t *>(ctx->subnets + ctx->hidden[l - 2].off_mask) : nullptr;
-    a.rankc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_rank) : nullptr;
+    a.sub = base + L.off_W;
+    a.rows = L.row_part ? tbl(base, ctx->hidden[l - 1].off_sorted) : nullptr;
+    a.cols = L.col_part ? tbl(base, ctx->hidden[l - 2].off_sorted) : nullptr;
+    a.slotr = L.row_part ? tbl(base, ctx->hidden[l - 1].off_slot) : nullptr;
+    a.slotc = L.col_part ? tbl(base, ctx->hidden[l - 2].off_slot) : nullptr;
+    a.maskc = L.col_part ? reinterpret_cast<const uint32_t *>(base + ctx->hidden[l - 2].off_mask) : nullptr;
+    a.rankc = L.col_part ? tbl(base, ctx->hidden[l - 2].off_rank) : nullptr;
     a.wordsc = L.col_part ? ctx->hidden[l - 2].words : 0;
     a.nr = L.R;
     a.nc = L.C;
@@ -398,6 +398,40 @@ static ist_status check_params(ist_ctx *ctx, const ist_params *p, const char *wh
     return IST_OK;
 }
 
+// Block tables of every hidden layer from the permutations, into the subnet buffer at `base`;
+// with checking on, IST_EPERM if some perm is not a permutation (synchronises the stream).
+static ist_status build_tables(ist_ctx *ctx, char *base, const int32_t *const *perm, hipStream_t st, const char *who)
+{
+    const int t = ctx->t, S = ctx->S;
+    if (ctx->checked) {
+        IST_HIP(hipMemsetAsync(ctx->errflag(), 0, sizeof(int32_t), st), "clear flag");
+        for (int l = 1; l < t; ++l)
+            IST_HIP(hipMemsetAsync(ctx->workspace + ctx->hidden[l - 1].off_invpos, 0xff,
+                                   sizeof(int32_t) * ctx->hidden[l - 1].N, st), "clear invpos");
+    }
+    for (int l = 1; l < t; ++l) {
+        const HiddenPlan &h = ctx->hidden[l - 1];
+        int32_t *invpos = reinterpret_cast<int32_t *>(ctx->workspace + h.off_invpos);
+        IST_RUN(KC_PERM_TABLES, launch_perm_tables(perm[l - 1], h.N, S, invpos,
+                                   reinterpret_cast<int32_t *>(base + h.off_sorted),
+                                   reinterpret_cast<int32_t *>(base + h.off_slot),
+                                   reinterpret_cast<int32_t *>(base + h.off_p2q),
+                                   reinterpret_cast<uint32_t *>(base + h.off_mask),
+                                   reinterpret_cast<int32_t *>(base + h.off_rank),
+                                   ctx->errflag(), st), "perm tables");
+        if (ctx->checked)
+            IST_RUN(KC_PERM_TABLES, launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");
+    }
+    if (ctx->checked) {
+        int32_t flag = 0;
+        IST_HIP(hipMemcpyAsync(&flag, ctx->errflag(), sizeof(flag), hipMemcpyDeviceToHost, st), "read flag");
+        IST_HIP(hipStreamSynchronize(st), "sync");
+        if (flag) return fail(ctx, IST_EPERM, std::string(who) + ": perm is not a permutation of 0..N_l-1");
+    }
+
+    return IST_OK;
+}
+
 ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *const *perm,
                          void *stream)
 {
@@ -412,35 +446,12 @@ ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *
     const int t = ctx->t, S = ctx->S, e = ctx->esz();
     ctx->partitioned = false;
 
-    if (ctx->checked) {
-        IST_HIP(hipMemsetAsync(ctx->errflag(), 0, sizeof(int32_t), st), "clear flag");
-        for (int l = 1; l < t; ++l)
-            IST_HIP(hipMemsetAsync(ctx->workspace + ctx->hidden[l - 1].off_invpos, 0xff,
-                                   sizeof(int32_t) * ctx->hidden[l - 1].N, st), "clear invpos");
-    }
-    for (int l = 1; l < t; ++l) {
-        const HiddenPlan &h = ctx->hidden[l - 1];
-        int32_t *invpos = reinterpret_cast<int32_t *>(ctx->workspace + h.off_invpos);
-        IST_RUN(KC_PERM_TABLES, launch_perm_tables(perm[l - 1], h.N, S, invpos,
-                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_sorted),
-                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_slot),
-                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_p2q),
-                                   reinterpret_cast<uint32_t *>(ctx->subnets + h.off_mask),
-                                   reinterpret_cast<int32_t *>(ctx->subnets + h.off_rank),
-                                   ctx->errflag(), st), "perm tables");
-        if (ctx->checked)
-            IST_RUN(KC_PERM_TABLES, launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");
-    }
-    if (ctx->checked) {
-        int32_t flag = 0;
-        IST_HIP(hipMemcpyAsync(&flag, ctx->errflag(), sizeof(flag), hipMemcpyDeviceToHost, st), "read flag");
-        IST_HIP(hipStreamSynchronize(st), "sync");
-        if (flag) return fail(ctx, IST_EPERM, "ist_partition: perm is not a permutation of 0..N_l-1");
-    }
+    ist_status ts = build_tables(ctx, ctx->subnets, perm, st, "ist_partition");
+    if (ts != IST_OK) return ts;
 
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
-        CopyArgs a = copy_args(ctx, l, params->W[l - 1]);
+        CopyArgs a = copy_args(ctx, ctx->subnets, l, params->W[l - 1]);
         IST_RUN(KC_PARTITION_COPY, launch_partition_copy(a, st), "partition copy");
         if (ctx->has_bias) {
             if (l < t) {
@@ -466,7 +477,7 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream)
     const int t = ctx->t, S = ctx->S, e = ctx->esz();
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
-        CopyArgs a = copy_args(ctx, l, params->W[l - 1]);
+        CopyArgs a = copy_args(ctx, ctx->subnets, l, params->W[l - 1]);
         IST_RUN(KC_MERGE_COPY, launch_merge_copy(a, st), "merge copy");
         if (ctx->has_bias) {
             if (l < t) {
@@ -481,6 +492,62 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream)
     return IST_OK;
 }
 
+ist_status ist_bind_spare(ist_ctx *ctx, void *spare_subnets, size_t bytes)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound) return fail(ctx, IST_ESTATE, "ist_bind_spare: call ist_bind first");
+    if (!spare_subnets) return fail(ctx, IST_EINVAL, "ist_bind_spare: null buffer");
+    if (bytes < ctx->subnets_bytes) return fail(ctx, IST_ENOMEM, "ist_bind_spare: buffer smaller than ist_subnets_bytes reports");
+    if (reinterpret_cast<uintptr_t>(spare_subnets) % kAlign) return fail(ctx, IST_EINVAL, "ist_bind_spare: buffer must be 256-byte aligned");
+    if (spare_subnets == ctx->subnets) return fail(ctx, IST_EINVAL, "ist_bind_spare: the spare must be a second buffer");
+    IST_HIP(hipMemset(spare_subnets, 0, ctx->layer[0].off_W), "ist_bind_spare: clear tables");
+    ctx->spare = static_cast<char *>(spare_subnets);
+    return IST_OK;
+}
+
+ist_status ist_resample(ist_ctx *ctx, const ist_params *params, const int32_t *const *perm, void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound || !ctx->partitioned) return fail(ctx, IST_ESTATE, "ist_resample: call ist_partition first");
+    if (!ctx->spare) return fail(ctx, IST_ESTATE, "ist_resample: call ist_bind_spare first");
+    ist_status ps = check_params(ctx, params, "ist_resample");
+    if (ps != IST_OK) return ps;
+    if (!perm) return fail(ctx, IST_EINVAL, "ist_resample: null perm list");
+    for (int l = 1; l < ctx->t; ++l)
+        if (!perm[l - 1]) return fail(ctx, IST_EINVAL, "ist_resample: null perm");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int t = ctx->t, S = ctx->S, e = ctx->esz();
+    // tables of the new partition go to the spare buffer; a rejected perm leaves everything as it was
+    ist_status ts = build_tables(ctx, ctx->spare, perm, st, "ist_resample");
+    if (ts != IST_OK) return ts;
+    for (int l = 1; l <= t; ++l) {
+        const LayerPlan &L = ctx->layer[l - 1];
+        CopyArgs o = copy_args(ctx, ctx->subnets, l, params->W[l - 1]);
+        CopyArgs n = copy_args(ctx, ctx->spare, l, params->W[l - 1]);
+        bool fused = false;
+        IST_RUN(KC_RESAMPLE, launch_resample_copy(o, n, &fused, st), "resample copy");
+        if (!fused) {
+            IST_RUN(KC_MERGE_COPY, launch_merge_copy(o, st), "merge copy");
+            IST_RUN(KC_PARTITION_COPY, launch_partition_copy(n, st), "partition copy");
+        }
+        if (ctx->has_bias) {
+            if (l < t) {
+                IST_RUN(KC_BIAS_COPY, launch_bias_rows(params->b[l - 1], ctx->subnets + L.off_b, o.rows, L.R * S, e, true, st),
+                        "merge bias");
+                IST_RUN(KC_BIAS_COPY, launch_bias_rows(params->b[l - 1], ctx->spare + L.off_b, n.rows, L.R * S, e, false, st),
+                        "partition bias");
+            } else {
+                IST_RUN(KC_BIAS_COPY, launch_bias_mean(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, ctx->dtype, st),
+                        "mean output bias");
+                IST_RUN(KC_BIAS_COPY, launch_bias_replicate(params->b[l - 1], ctx->spare + L.off_b, L.R, S, e, st),
+                        "replicate output bias");
+            }
+        }
+    }
+    std::swap(ctx->subnets, ctx->spare);
+    return IST_OK;
+}
+
 ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, void *dstb, void *stream)
 {
     if (!ctx) return IST_EINVAL;
@@ -489,8 +556,8 @@ ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, voi
     hipStream_t st = static_cast<hipStream_t>(stream);
     const LayerPlan &L = ctx->layer[l - 1];
     const int e = ctx->esz();
-    const int32_t *pr = L.row_part ? tbl(ctx, ctx->hidden[l - 1].off_p2q) : nullptr;
-    const int32_t *pc = L.col_part ? tbl(ctx, ctx->hidden[l - 2].off_p2q) : nullptr;
+    const int32_t *pr = L.row_part ? tbl(ctx->subnets, ctx->hidden[l - 1].off_p2q) : nullptr;
+    const int32_t *pc = L.col_part ? tbl(ctx->subnets, ctx->hidden[l - 2].off_p2q) : nullptr;
     const char *blk = ctx->subnets + L.off_W + (size_t)s * L.R * L.C * e;
     IST_HIP(launch_export(blk, dstW, L.R, L.C, pr, (int64_t)s * L.R, pc, (int64_t)s * L.C, L.transposed, e, st),
             "export W");

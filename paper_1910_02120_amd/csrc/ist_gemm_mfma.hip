@@ -304,7 +304,6 @@ template <typename D, int CPR>
 __device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk, float (&val)[8],
                                const float (&bias8)[8], int label)
 {
-    using T = typename D::T;
     const bool rowok = m < a.M;
     const int nv = !rowok ? 0 : (a.N - n0 >= 8 ? 8 : (a.N - n0 > 0 ? a.N - n0 : 0));
 #pragma unroll

@@ -85,6 +85,7 @@ struct ist_ctx {
     bool fused_out = false;   // wide output layer: logits are never stored
     size_t off_pmax = 0, off_psum = 0, off_qmax = 0, off_qsum = 0, off_zlabel = 0, off_lse = 0; int32_t nb_max = 0;
     char *subnets = nullptr;
+    char *spare = nullptr;      // second subnet buffer: target of ist_resample, then swapped in
     char *workspace = nullptr;
     bool bound = false, partitioned = false;
     int32_t checked = 0;
@@ -105,7 +106,7 @@ namespace ist {
 enum KernelClass {
     KC_PERM_TABLES = 0, KC_PARTITION_COPY, KC_MERGE_COPY, KC_BIAS_COPY, KC_GEMM_FWD, KC_GEMM_BWD_DATA,
     KC_GEMM_UPDATE, KC_SOFTMAX_XENT, KC_LOSS_REDUCE, KC_BIAS_UPDATE, KC_CSR_FORWARD, KC_CSR_UPDATE,
-    KC_NORM, KC_COUNT
+    KC_NORM, KC_RESAMPLE, KC_COUNT
 };
 
 // What the last launcher call ran: kernel label (launch configuration), algorithmic flops and
@@ -140,6 +141,7 @@ struct CopyArgs {
 };
 hipError_t launch_partition_copy(const CopyArgs &a, hipStream_t st);
 hipError_t launch_merge_copy(const CopyArgs &a, hipStream_t st);
+hipError_t launch_resample_copy(const CopyArgs &old_part, const CopyArgs &new_part, bool *fused, hipStream_t st);
 hipError_t launch_bias_rows(void *b, void *sub, const int32_t *rows, int64_t n, int esz, bool scatter,
                             hipStream_t st);
 hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G, int esz,

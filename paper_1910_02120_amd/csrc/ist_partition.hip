@@ -523,6 +523,134 @@ hipError_t launch_merge_copy(const CopyArgs &a, hipStream_t st)
 }
 
 // ----------------------------------------------------------------------------
+// re-sampling between rounds: merge of the old partition and partition by the new permutation in
+// one pass over the full matrix (the row that merge writes is the row partition would read back)
+// ----------------------------------------------------------------------------
+// first layer: W[r][:] = old[slot_old[r]][:], new[slot_new[r]][:] = the same row
+template <typename E>
+__global__ __launch_bounds__(256) void k_resample_rows(E *__restrict__ W, int64_t ld, const E *__restrict__ sub_old,
+                                                       E *__restrict__ sub_new, const int32_t *__restrict__ slot_old,
+                                                       const int32_t *__restrict__ slot_new, int64_t nrows, int64_t nc)
+{
+    for (int64_t r = blockIdx.x; r < nrows; r += gridDim.x) {
+        const int64_t Po = slot_old[r], Pn = slot_new[r];
+        if (Po < 0 || Po >= nrows || Pn < 0 || Pn >= nrows) continue;   // only with non-permutation tables
+        const uint4 *src = reinterpret_cast<const uint4 *>(sub_old + Po * nc);
+        uint4 *full = reinterpret_cast<uint4 *>(W + r * ld);
+        uint4 *dst = reinterpret_cast<uint4 *>(sub_new + Pn * nc);
+        const int64_t n16 = nc * (int64_t)sizeof(E) / 16;
+        for (int64_t c = threadIdx.x; c < n16; c += 256) {
+            const uint4 v = src[c];
+            full[c] = v;
+            dst[c] = v;
+        }
+    }
+}
+
+// middle layers: k_mid_lds with both directions on the staged chunk
+template <typename E>
+__global__ __launch_bounds__(256) void k_resample_mid(E *__restrict__ W, int64_t ld, const E *__restrict__ sub_old,
+                                                      E *__restrict__ sub_new, const int32_t *__restrict__ slotr_old,
+                                                      const int32_t *__restrict__ slotr_new,
+                                                      const int32_t *__restrict__ cols_old,
+                                                      const int32_t *__restrict__ cols_new,
+                                                      const int32_t *__restrict__ rank_old,
+                                                      const int32_t *__restrict__ rank_new, int64_t words, int64_t nr,
+                                                      int64_t nc, int64_t N_in, int32_t G)
+{
+    constexpr int EPC = 16 / sizeof(E);
+    constexpr int PER = kMidChunk / EPC / 256;
+    __shared__ __attribute__((aligned(16))) E buf[kMidChunk];
+    const int64_t Po = slotr_old[blockIdx.x], Pn = slotr_new[blockIdx.x];
+    if (Po < 0 || Po >= nr * G || Pn < 0 || Pn >= nr * G) return;
+    const int go = (int)(Po / nr), gn = (int)(Pn / nr);
+    uint4 *full = reinterpret_cast<uint4 *>(W + (int64_t)blockIdx.x * ld);
+    const E *pack_old = sub_old + Po * nc;
+    E *pack_new = sub_new + Pn * nc;
+    const int32_t *co = cols_old + (int64_t)go * nc, *cn = cols_new + (int64_t)gn * nc;
+    const int32_t *ro = rank_old + (int64_t)go * words, *rn = rank_new + (int64_t)gn * words;
+    const int64_t row_pieces = N_in / EPC;
+    auto clampq = [&](int64_t q) { return q < 0 ? (int64_t)0 : (q > nc ? nc : q); };
+    uint4 nxt[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int64_t c = threadIdx.x + 256 * u;
+        nxt[u] = c < row_pieces ? full[c] : uint4{0, 0, 0, 0};
+    }
+    for (int64_t c0 = 0; c0 < N_in; c0 += kMidChunk) {
+        const int64_t cend = c0 + kMidChunk < N_in ? c0 + kMidChunk : N_in;
+        const int64_t qlo_o = clampq(ro[c0 >> 5]), qhi_o = cend < N_in ? clampq(ro[cend >> 5]) : nc;
+        const int64_t qlo_n = clampq(rn[c0 >> 5]), qhi_n = cend < N_in ? clampq(rn[cend >> 5]) : nc;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) reinterpret_cast<uint4 *>(buf)[threadIdx.x + 256 * u] = nxt[u];
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int64_t c = (c0 + kMidChunk) / EPC + threadIdx.x + 256 * u;
+            nxt[u] = c < row_pieces ? full[c] : uint4{0, 0, 0, 0};
+        }
+        for (int64_t q = qlo_o + threadIdx.x; q < qhi_o; q += 256) {
+            const int64_t off = (int64_t)co[q] - c0;
+            if (off >= 0 && off < cend - c0) buf[off] = pack_old[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int64_t c = c0 / EPC + threadIdx.x + 256 * u;
+            if (c < row_pieces) full[c] = reinterpret_cast<const uint4 *>(buf)[threadIdx.x + 256 * u];
+        }
+        for (int64_t q = qlo_n + threadIdx.x; q < qhi_n; q += 256) {
+            const int64_t off = (int64_t)cn[q] - c0;
+            if (off >= 0 && off < cend - c0) pack_new[q] = buf[off];
+        }
+        __syncthreads();
+    }
+}
+
+template <typename E>
+static bool resample_typed(const CopyArgs &o, const CopyArgs &n, hipStream_t st)
+{
+    constexpr int EPC = 16 / sizeof(E);
+    E *W = static_cast<E *>(o.W);
+    const E *so = static_cast<const E *>(o.sub);
+    E *sn = static_cast<E *>(n.sub);
+    const bool aligned = reinterpret_cast<uintptr_t>(W) % 16 == 0 && reinterpret_cast<uintptr_t>(so) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(sn) % 16 == 0 && o.ld % EPC == 0 && o.N_in % EPC == 0;
+    if (o.transposed || !aligned) return false;
+    const double esz = sizeof(E);
+    const double sub_b = (double)o.G * o.nr * o.nc * esz, full_b = (double)o.N_out * o.N_in * esz;
+    if (!o.cols) {   // first layer
+        if (!o.slotr || !n.slotr || o.nc % EPC || o.nr * o.G != o.N_out) return false;
+        tag_kernel("k_resample_rows", 0.0, 3.0 * sub_b);
+        const int64_t nrows = o.N_out;
+        hipLaunchKernelGGL((k_resample_rows<E>), dim3((unsigned)(nrows < 65536 ? nrows : 65536)), dim3(256), 0, st, W, o.ld,
+                           so, sn, o.slotr, n.slotr, nrows, o.nc);
+        return true;
+    }
+    const int64_t all_rows = o.nr * o.G;
+    if (o.rows) {    // middle layer
+        if (!(o.slotr && n.slotr && o.rankc && n.rankc && o.N_in == o.ld && o.N_in % 32 == 0 && all_rows == o.N_out &&
+              all_rows < 0x7fffffffLL))
+            return false;
+        tag_kernel("k_resample_mid", 0.0, 2.0 * full_b + 2.0 * sub_b);
+        hipLaunchKernelGGL((k_resample_mid<E>), dim3((unsigned)all_rows), dim3(256), 0, st, W, o.ld, so, sn, o.slotr, n.slotr,
+                           o.cols, n.cols, o.rankc, n.rankc, o.wordsc, o.nr, o.nc, o.N_in, o.G);
+        return true;
+    }
+    // last layer: every line of W is owned, merge and partition each move it once already, and one
+    // workgroup touching the blocks of both buffers in all S subnets measured slower than the two passes
+    return false;
+}
+
+// Fused merge(old) + partition(new) of one layer; *fused = false when the shape is not covered and
+// the caller has to run the two copies one after the other.
+hipError_t launch_resample_copy(const CopyArgs &o, const CopyArgs &n, bool *fused, hipStream_t st)
+{
+    *fused = o.esz == 2 ? resample_typed<uint16_t>(o, n, st) : resample_typed<uint32_t>(o, n, st);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------
 // output bias: replicate on partition, mean on merge
 // ----------------------------------------------------------------------------
 template <typename E>

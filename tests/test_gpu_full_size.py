@@ -210,3 +210,49 @@ def test_large_workload_sampled_parity(name, normalize):
                 del Wg
             assert np.array_equal(H.bits(new[i:i + 1]), want), (name, l, int(r))
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
+def test_resample_at_full_size_equals_merge_then_partition(name):
+    """Bit-exact agreement of the one-pass re-sampling with the two calls it replaces, on the whole
+    of every weight matrix and on sampled blocks of the new subnets, after one (small-batch) local
+    step so that the subnets differ from the full network."""
+    cfg = gen.scaled(C[name], B=8, k=1)
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(gen.SEED_BASE + 7 * cfg.idx)
+    rng = np.random.default_rng(100 + cfg.idx)
+    dW, db = _device_weights(cfg, dev, g)
+    dperm = [torch.from_numpy(p).to(dev) for p in gen.make_perms(cfg, 0)]
+    perm1 = [torch.from_numpy(p).to(dev) for p in gen.make_perms(cfg, 1)]
+    if cfg.input == "csr":
+        rp, ci, va, y = gen.make_csr_batches(cfg)
+        data = dict(csr=(torch.from_numpy(rp).to(dev), torch.from_numpy(ci).to(dev), H.to_dev(va, cfg.dtype)), X=None)
+    else:
+        X, y = gen.make_dense_batches(cfg)
+        data = dict(X=H.to_dev(X, cfg.dtype), csr=None)
+    dy = torch.from_numpy(y.reshape(-1)).to(dev)
+    from paper_1910_02120_amd import ISTContext
+    ctxs = [ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B) for _ in range(2)]
+    for c in ctxs:
+        c.partition(dW, db, dperm)
+        c.subnet_steps(dy, 0.5, 1, cfg.B, **data)
+    a, b = ctxs
+    Wb = [w.clone() for w in dW]
+    bb = [x.clone() for x in db]
+    a.resample(dW, db, perm1)
+    b.merge(Wb, bb)
+    b.partition(Wb, bb, perm1)
+    torch.cuda.synchronize()
+    for l in range(cfg.t):
+        assert torch.equal(dW[l], Wb[l]), (name, l)
+        assert torch.equal(db[l], bb[l]), (name, l, "bias")
+    for l in range(1, cfg.t + 1):
+        for s in rng.choice(cfg.S, size=2, replace=False):
+            wa, xa = a.subnet_export(int(s), l)
+            wb, xb = b.subnet_export(int(s), l)
+            torch.cuda.synchronize()
+            assert torch.equal(wa, wb) and torch.equal(xa, xb), (name, l, int(s))
+            del wa, wb
+    a.close()
+    b.close()

@@ -300,3 +300,71 @@ def test_k_local_steps_with_standardisation_match_oracle(name):
     np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
     print(f"{name} (standardised): worst parameter rel err {worst:.3e} (tol {tol})")
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "cfg5-small",
+                                  "csr-f32", "wide-out-f32", "deep-bf16", "width-one-blocks-f32", "cfg1-nobias-S1"])
+def test_resample_equals_merge_then_partition(name):
+    """ist_resample leaves the full network and the new subnets exactly as ist_merge followed by
+    ist_partition with the new permutation would (bit for bit), twice in a row (the two subnet
+    buffers change roles), and training continues identically afterwards."""
+    cfg = SHAPES[name]
+    has_bias = "nobias" not in name
+    P = H.Problem(cfg, has_bias=has_bias, dev=_dev())
+    a, b = P.context(), P.context()
+    Wa, Wb = [w.clone() for w in P.dW], [w.clone() for w in P.dW]
+    ba = [x.clone() for x in P.db] if has_bias else None
+    bb = [x.clone() for x in P.db] if has_bias else None
+    a.partition(Wa, ba, P.dperm)
+    b.partition(Wb, bb, P.dperm)
+    for rnd in (1, 2):
+        P.gpu_steps(a, loss=False)
+        P.gpu_steps(b, loss=False)
+        perm = [torch.from_numpy(p).to(_dev()) for p in gen.make_perms(cfg, rnd)]
+        a.profile_enable(True)
+        a.profile_reset()
+        a.resample(Wa, ba, perm)
+        labels = {k["label"] for k in a.profile_kernels()}
+        a.profile_enable(False)
+        if name in ("cfg1", "cfg3-small", "cfg4-small"):   # aligned shapes take the one-pass kernels
+            assert {"k_resample_rows", "k_resample_mid"} <= labels, labels
+        b.merge(Wb, bb)
+        b.partition(Wb, bb, perm)
+        torch.cuda.synchronize()
+        for l in range(cfg.t):
+            assert torch.equal(Wa[l], Wb[l]), (name, rnd, l, "merged weights")
+            if has_bias:
+                assert torch.equal(ba[l], bb[l]), (name, rnd, l, "merged bias")
+        ga, gb = H.export_all(a, cfg), H.export_all(b, cfg)
+        for s in range(cfg.S):
+            for l in range(cfg.t):
+                assert torch.equal(ga[s][0][l], gb[s][0][l]), (name, rnd, s, l, "new subnet weights")
+                if has_bias:
+                    assert torch.equal(ga[s][1][l], gb[s][1][l]), (name, rnd, s, l, "new subnet bias")
+    a.close()
+    b.close()
+
+
+def test_resample_rejects_a_bad_permutation_and_keeps_its_state():
+    from paper_1910_02120_amd import ISTError
+    cfg = SHAPES["ragged-f32"]
+    P = H.Problem(cfg, dev=_dev())
+    ctx = P.context()
+    W, bsv = [w.clone() for w in P.dW], [x.clone() for x in P.db]
+    ctx.set_checked(True)
+    ctx.partition(W, bsv, P.dperm)
+    P.gpu_steps(ctx, loss=False)
+    before = H.export_all(ctx, cfg)
+    W0 = [w.clone() for w in W]
+    bad = [p.clone() for p in P.dperm]
+    bad[0][1] = bad[0][2]
+    with pytest.raises(ISTError) as e:
+        ctx.resample(W, bsv, bad)
+    assert e.value.status == -3
+    after = H.export_all(ctx, cfg)
+    for l in range(cfg.t):
+        assert torch.equal(W[l], W0[l])
+        for s in range(cfg.S):
+            assert torch.equal(before[s][0][l], after[s][0][l])
+    ctx.resample(W, bsv, P.dperm)          # and a good one still works
+    ctx.close()
