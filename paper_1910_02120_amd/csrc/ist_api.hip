@@ -219,7 +219,7 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         ctx->off_lse = w; w = align_up(w + sizeof(float) * rows);
     }
     ctx->off_zeros = w; w = align_up(w + 256);   // stays zero: source of out-of-range operand chunks
-    ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)S * max_B);
+    ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)kLossSlots * S * max_B);
     ctx->off_bitmap = w;
     if (d->input == IST_CSR)
         w = align_up(w + sizeof(uint32_t) * (size_t)S * ctx->dims[0] * ((max_B + 31) / 32));
@@ -589,10 +589,13 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int t = ctx->t, S = ctx->S, e = ctx->esz(), B = bt->B, dt = ctx->dtype;
     char *ws = ctx->workspace, *sb = ctx->subnets;
-    float *rowloss = reinterpret_cast<float *>(ws + ctx->off_rowloss);
+    float *rowloss0 = reinterpret_cast<float *>(ws + ctx->off_rowloss);   // [kLossSlots][S][B]
+
 
     for (int j = 0; j < k; ++j) {
         const int64_t row0 = (int64_t)j * bt->stride_k;
+        float *rowloss = rowloss0 + (size_t)(j % kLossSlots) * S * B;
+        int out_splits = 1;
         // ---------------- forward ----------------
         for (int l = 1; l <= t; ++l) {
             const LayerPlan &L = ctx->layer[l - 1];
@@ -651,17 +654,37 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                                     ctx->norm_eps, dt, st), "standardise (forward)");
                 continue;
             }
+            if (l == t && L.R <= kXentRowsMaxC) {
+                // narrow output layer: a k-split product leaves its partial sums to the cross-entropy kernel
+                a.keep_partial = 1;
+                out_splits = gemm_splits(dt, EPI_FWD_LOGITS, a);
+            }
             IST_RUN(KC_GEMM_FWD, launch_gemm(dt, l == t ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st), "forward gemm");
         }
         // ---------------- loss and dz_t ----------------
-        if (ctx->fused_out) {
-            if (loss_out) IST_RUN(KC_LOSS_REDUCE, launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
-        } else {
+        if (!ctx->fused_out) {
             const LayerPlan &L = ctx->layer[t - 1];
-            IST_RUN(KC_SOFTMAX_XENT, launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
-                                        bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, L.ldr, dt, st),
-                    "softmax cross-entropy");
-            if (loss_out) IST_RUN(KC_LOSS_REDUCE, launch_loss_reduce(rowloss, loss_out + j, k, S, B, st), "loss reduce");
+            if (L.R > kXentRowsMaxC) {
+                IST_RUN(KC_SOFTMAX_XENT, launch_softmax_xent(reinterpret_cast<const float *>(ws + L.off_act), bt->y + row0,
+                                            bt->stride_s, ws + L.off_dz, rowloss, S, B, L.R, L.ldr, dt, st),
+                        "softmax cross-entropy");
+            } else if (out_splits > 1) {
+                const int64_t mn = (int64_t)B * L.R;
+                IST_RUN(KC_SOFTMAX_XENT, launch_xent_rows(reinterpret_cast<const float *>(ws + ctx->off_partial), out_splits, mn,
+                                            out_splits * mn, L.R, ctx->has_bias ? sb + L.off_b : nullptr, L.R, bt->y + row0,
+                                            bt->stride_s, ws + L.off_dz, L.ldr, rowloss, S, B, (int32_t)L.R, dt, st),
+                        "softmax cross-entropy (from partial products)");
+            } else {
+                IST_RUN(KC_SOFTMAX_XENT, launch_xent_rows(reinterpret_cast<const float *>(ws + L.off_act), 1, 0,
+                                            (int64_t)B * L.ldr, L.ldr, nullptr, 0, bt->y + row0, bt->stride_s,
+                                            ws + L.off_dz, L.ldr, rowloss, S, B, (int32_t)L.R, dt, st),
+                        "softmax cross-entropy");
+            }
+        }
+        // the row losses of up to kLossSlots steps are averaged by one launch
+        if (loss_out && (j % kLossSlots == kLossSlots - 1 || j == k - 1)) {
+            const int j0 = j - j % kLossSlots;
+            IST_RUN(KC_LOSS_REDUCE, launch_loss_reduce(rowloss0, loss_out + j0, k, S, B, j - j0 + 1, st), "loss reduce");
         }
         // ---------------- backward + update, top layer first ----------------
         for (int l = t; l >= 1; --l) {

@@ -116,13 +116,23 @@ hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_
 }
 
 // IST_GEMM=generic in the environment selects the plain FMA kernel (debugging aid).
-hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
+static bool force_generic()
 {
-    static const bool force_generic = [] {
+    static const bool on = [] {
         const char *e = getenv("IST_GEMM");
         return e && std::string(e) == "generic";
     }();
-    return force_generic ? launch_gemm_generic(dtype, epi, a, st) : launch_gemm_mfma(dtype, epi, a, st);
+    return on;
+}
+
+hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
+{
+    return force_generic() ? launch_gemm_generic(dtype, epi, a, st) : launch_gemm_mfma(dtype, epi, a, st);
+}
+
+int gemm_splits(int dtype, int epi, const GemmArgs &a)
+{
+    return force_generic() ? 1 : gemm_splits_mfma(dtype, epi, a);
 }
 
 }  // namespace ist

@@ -832,6 +832,22 @@ static void launch_small(const GemmArgs &a, const SplitPlan &p, bool vecC, hipSt
                              p.k_per_split, st);
 }
 
+// the plan of one launch: k is split only where the epilogue allows it and the scratch buffer is large enough
+static SplitPlan plan_for(const GemmArgs &a, int epi, int esz)
+{
+    const bool can_split = epi != EPI_UPDATE && epi != EPI_LSE && epi != EPI_DZ && a.partial != nullptr;
+    SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
+    if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes)
+        p = plan_gemm(a.M, a.N, a.K, a.G, false, esz);
+    return p;
+}
+
+int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a)
+{
+    if (a.M <= 0 || a.N <= 0 || a.G <= 0) return 1;
+    return plan_for(a, epi, dtype == IST_BF16 ? 2 : 4).splits;
+}
+
 template <typename D, bool AK, bool BKC, int EPI, bool VEC>
 static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
 {
@@ -841,10 +857,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
     static thread_local char lab[40];
     snprintf(lab, sizeof(lab), "%s_%s%s", kEpi[EPI], esz == 2 ? "bf16" : "f32", VEC ? "" : "_novec");
     s_label = lab;
-    const bool can_split = EPI != EPI_UPDATE && EPI != EPI_LSE && EPI != EPI_DZ && a.partial != nullptr;
-    SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
-    if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes)
-        p = plan_gemm(a.M, a.N, a.K, a.G, false, esz);
+    const SplitPlan p = plan_for(a, EPI, esz);
     if (p.tile == 128) {
         constexpr int KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
         // bf16 forward / backward-data: 256x128 blocks (each wave 128x64) halve the LDS traffic
@@ -886,6 +899,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
         pa.C = a.partial; pa.ldc = a.N; pa.gC = (int64_t)a.M * a.N;
         const bool vecP = vec_c_ok(pa, EPI_PARTIAL, esz);
         launch_small<D, AK, BKC, EPI_PARTIAL, VEC>(pa, p, vecP, st);
+        if (a.keep_partial) return hipGetLastError();
         const int64_t units = (int64_t)a.M * ((a.N + 7) / 8);
         dim3 g2((unsigned)((units + 255) / 256), 1, (unsigned)a.G);
         hipLaunchKernelGGL((k_splitk_finish<D, EPI>), g2, dim3(256), 0, st, a, a.partial, p.splits, vecC);

@@ -169,6 +169,7 @@ struct GemmArgs {
     const void *mask; int64_t ldm, gMask;     // EPI_BWD_DATA: keep where mask[m][n] > 0
     float lr;                                 // EPI_UPDATE: C = C - lr * acc
     float *partial; size_t partial_bytes;     // split-K scratch (fp32 partial products), may be null
+    int32_t keep_partial;                     // host flag: a k-split launch leaves the partial products unfinished
     const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
     // EPI_LSE / EPI_DZ (softmax cross-entropy over a wide output layer, logits never stored)
     const int32_t *y; int64_t gY;             // labels of the batch rows, per-group stride
@@ -186,12 +187,25 @@ constexpr int kLseChunksHost = 32;   // second-level partials per row (matches t
 struct SplitPlan { int tile; int splits; int k_per_split; int kg; int64_t tiles; };
 SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz);
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+// Number of k-splits launch_gemm uses for this product (1: none).  With a.keep_partial set, a split
+// launch only writes a.partial, laid out [g * splits + sp][M][N] in fp32 without the bias, and the
+// caller's next kernel adds the splits up; unsplit launches are not affected.
+int gemm_splits(int dtype, int epi, const GemmArgs &a);
 hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
+int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
                                int64_t ld, int dtype, hipStream_t st);
+// The same for at most kXentRowsMaxC classes, reading either stored logits (splits == 1, bias == null)
+// or the partial products of a k-split forward product (element strides between splits / groups / rows).
+constexpr int kXentRowsMaxC = 256;
+hipError_t launch_xent_rows(const float *z, int32_t splits, int64_t split_stride, int64_t g_stride, int64_t ldz,
+                            const void *bias, int64_t gBias, const int32_t *y, int64_t y_stride_g, void *dz,
+                            int64_t ld, float *rowloss, int32_t G, int32_t B, int32_t Cn, int dtype, hipStream_t st);
+// row losses of up to this many steps wait in the workspace for one reduction launch
+constexpr int kLossSlots = 16;
 // Section 2.2 standardisation of hidden-neuron inputs over the mini-batch, per subnet g and column r:
 // forward: zh = (z - mean_b z) / sqrt(var_b z + eps) -> dtype, h = max(zh, 0), isg = 1 / sigma;
 // backward (in place on dz, which holds dzh = dh * [zh > 0]):
@@ -200,8 +214,9 @@ hipError_t launch_norm_forward(const float *z, void *zh, void *h, float *isg, in
                                int64_t ld, float eps, int dtype, hipStream_t st);
 hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int32_t G, int32_t B, int64_t R,
                                 int64_t ld, int dtype, hipStream_t st);
+// loss_out[g * out_stride_g + j] = mean_b rowloss[j][g][b], j < nsteps
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
-                              int32_t G, int32_t B, hipStream_t st);
+                              int32_t G, int32_t B, int32_t nsteps, hipStream_t st);
 struct BiasJob { void *bias; const void *dz; int64_t R, ld; int32_t blk0; };
 constexpr int kMaxBiasJobs = 16;
 struct BiasArgs { BiasJob job[kMaxBiasJobs]; int32_t njobs, B, G; float lr; };

@@ -87,23 +87,93 @@ hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_
     return hipGetLastError();
 }
 
-// loss_out[g * out_stride_g] = mean_b rowloss[g][b]; one wave per subnet, fixed order.
+// Narrow output layer (Cn <= 256): one wave per (subnet g, sample b), four per workgroup, the
+// classes lane, lane + 64, ... of the row in registers.  The logits are either stored values
+// (splits == 1, bias already added) or the sum, in split order, of the fp32 partial products
+// of a k-split forward product plus the bias, so that such a product needs no finishing pass.
+template <typename D>
+__global__ __launch_bounds__(256) void k_xent_rows(const float *__restrict__ z, int32_t splits, int64_t split_stride,
+                                                   int64_t g_stride, int64_t ldz,
+                                                   const typename D::T *__restrict__ bias, int64_t gBias,
+                                                   const int32_t *__restrict__ y, int64_t y_stride_g,
+                                                   typename D::T *__restrict__ dz, int64_t ld,
+                                                   float *__restrict__ rowloss, int32_t G, int32_t B, int32_t Cn)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (int64_t)G * B) return;
+    const int g = (int)(row / B), b = (int)(row % B);
+    const float *zr = z + (int64_t)g * g_stride + (int64_t)b * ldz;
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = lane + 64 * i;
+        float acc = 0.0f;
+        if (c < Cn) {
+#pragma unroll 8
+            for (int sp = 0; sp < splits; ++sp) acc += zr[(int64_t)sp * split_stride + c];
+            if (bias) acc += D::ld(bias + (int64_t)g * gBias + c);
+        }
+        v[i] = c < Cn ? acc : -INFINITY;
+    }
+    const int32_t label = y[(int64_t)g * y_stride_g + b];
+    const float mx = wave_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+    float e[4], se = 0.0f, zl = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = lane + 64 * i;
+        e[i] = c < Cn ? __expf(v[i] - mx) : 0.0f;
+        se += e[i];
+        zl += (c < Cn && c == label) ? v[i] : 0.0f;
+    }
+    se = wave_sum(se);
+    zl = wave_sum(zl);
+    const float inv = 1.0f / se, invB = 1.0f / (float)B;
+    typename D::T *out = dz + ((int64_t)g * B + b) * ld;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = lane + 64 * i;
+        if (c < Cn) out[c] = D::cvt((e[i] * inv - (c == label ? 1.0f : 0.0f)) * invB);
+    }
+    if (lane == 0) rowloss[row] = __logf(se) + mx - ((label >= 0 && label < Cn) ? zl : mx);
+}
+
+hipError_t launch_xent_rows(const float *z, int32_t splits, int64_t split_stride, int64_t g_stride, int64_t ldz,
+                            const void *bias, int64_t gBias, const int32_t *y, int64_t y_stride_g, void *dz,
+                            int64_t ld, float *rowloss, int32_t G, int32_t B, int32_t Cn, int dtype, hipStream_t st)
+{
+    if (Cn > 256 || splits < 1) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(((int64_t)G * B + 3) / 4));
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL((k_xent_rows<BF16>), grid, dim3(256), 0, st, z, splits, split_stride, g_stride, ldz,
+                           static_cast<const uint16_t *>(bias), gBias, y, y_stride_g, static_cast<uint16_t *>(dz), ld,
+                           rowloss, G, B, Cn);
+    else
+        hipLaunchKernelGGL((k_xent_rows<F32>), grid, dim3(256), 0, st, z, splits, split_stride, g_stride, ldz,
+                           static_cast<const float *>(bias), gBias, y, y_stride_g, static_cast<float *>(dz), ld,
+                           rowloss, G, B, Cn);
+    return hipGetLastError();
+}
+
+// loss_out[g * out_stride_g + j] = mean_b rowloss[j][g][b] for the steps j < nsteps of a call whose
+// row losses are still waiting; one wave per (subnet, step), fixed order.
 __global__ __launch_bounds__(64) void k_loss_reduce(const float *__restrict__ rowloss,
                                                     float *__restrict__ loss_out,
-                                                    int64_t out_stride_g, int32_t B)
+                                                    int64_t out_stride_g, int32_t G, int32_t B)
 {
-    const int g = blockIdx.x;
+    const int g = blockIdx.x, j = blockIdx.y;
+    const float *r = rowloss + ((int64_t)j * G + g) * B;
     float acc = 0.0f;
-    for (int b = threadIdx.x; b < B; b += 64) acc += rowloss[(int64_t)g * B + b];
+    for (int b = threadIdx.x; b < B; b += 64) acc += r[b];
     acc = wave_sum(acc);
-    if (threadIdx.x == 0) loss_out[(int64_t)g * out_stride_g] = acc / (float)B;
+    if (threadIdx.x == 0) loss_out[(int64_t)g * out_stride_g + j] = acc / (float)B;
 }
 
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g, int32_t G,
-                              int32_t B, hipStream_t st)
+                              int32_t B, int32_t nsteps, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_loss_reduce, dim3((unsigned)G), dim3(64), 0, st, rowloss, loss_out,
-                       out_stride_g, B);
+    hipLaunchKernelGGL(k_loss_reduce, dim3((unsigned)G, (unsigned)nsteps), dim3(64), 0, st, rowloss, loss_out,
+                       out_stride_g, G, B);
     return hipGetLastError();
 }
 

@@ -45,6 +45,10 @@ SHAPES = {
     "csr-bf16-even": _mk("csr-bf16-even", "cfg5", dims=(1000, 512, 77), S=4, B=21, k=2, nnz_per_row=12, lr=0.5),
     "csr-bf16-odd": _mk("csr-bf16-odd", "cfg5", dims=(777, 64, 50), S=8, B=10, k=2, nnz_per_row=7, lr=0.5),
     "speech-small": _mk("speech-small", "speech8192", dims=(256, 512, 512, 512, 35), k=3, lr=0.05),
+    # more steps than row-loss slots of one reduction launch, and a class count that spans three
+    # 64-wide lane groups of the narrow-output cross-entropy kernel; 300 classes take the wide kernel
+    "many-steps-f32": _mk("many-steps-f32", "cfg2", dims=(48, 64, 130), S=2, B=10, k=19, lr=0.05),
+    "mid-out-bf16": _mk("mid-out-bf16", "cfg3", dims=(64, 128, 300), S=4, B=12, k=2, lr=0.05),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
