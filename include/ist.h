@@ -157,6 +157,20 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream);
 ist_status ist_bind_spare(ist_ctx *ctx, void *spare_subnets, size_t spare_bytes);
 ist_status ist_resample(ist_ctx *ctx, const ist_params *params, const int32_t *const *perm, void *stream);
 
+/*
+ * ist_forward_full - the forward pass of the FULL network (every neuron of every layer, no
+ * partition): logits = W_t f_{t-1} + b_t with f_l = ReLU(W_l f_{l-1} + b_l), the network of
+ * Section 2.1 that the subnets are cut from and merged back into; with `normalize` set the
+ * inputs of the hidden neurons are standardised with the statistics of this batch (Section 2.2:
+ * after training, mu and sigma are computed with the full network over a subset of the data).
+ * For evaluation between rounds.  Uses samples 0..B-1 of `batch` (x rows or CSR rows 0..B-1;
+ * y and the strides are ignored), B <= max_B.  logits: [device] float [B][N_t].  Same storage
+ * and accumulation types as ist_subnet_steps.  Needs ist_bind only; it overwrites the workspace
+ * (not the subnets), so it must not run concurrently with ist_subnet_steps on another stream.
+ */
+ist_status ist_forward_full(ist_ctx *ctx, const ist_params *params, const ist_batch *batch,
+                            float *logits /*[device]*/, void *stream);
+
 /* Canonical view of one subnet's layer l (1..t) for inspection and tests:
  * dstW [device] row-major [rows][cols] with rows/cols in the order of the
  * permutation block (H_l^s order), dstb [device] [rows] or NULL. */

@@ -17,7 +17,8 @@
  *     ist_oracle_scatter.
  *   - Appendix B, third bullet: the local step is w <- z - eta * grad l(z).
  *   - Section 2.2: the n^2 factor is dropped; the hot path is the plain narrow
- *     MLP (the per-neuron normalisation is a later extension, not built here).
+ *     MLP, optionally with the per-neuron standardisation of that section
+ *     (ist_oracle_subnet_sgd_norm).
  *
  * Readings where the paper is silent (all restated in the design notes):
  *   ReLU hidden activations with ReLU'(0) = 0, mean softmax cross-entropy loss,
@@ -60,6 +61,10 @@ static double round_store(double x, int mode)
 }
 
 double ist_oracle_round(double x, int32_t mode) { return round_store(x, mode); }
+void ist_oracle_round_array(double *x, int64_t n, int32_t mode)
+{
+    for (int64_t i = 0; i < n; ++i) x[i] = round_store(x[i], mode);
+}
 
 /* ------------------------------------------------- blocks, partition, merge */
 

@@ -62,6 +62,8 @@ def _load():
     p = C.c_void_p
     lib.ist_oracle_round.restype = C.c_double
     lib.ist_oracle_round.argtypes = [C.c_double, C.c_int32]
+    lib.ist_oracle_round_array.restype = None
+    lib.ist_oracle_round_array.argtypes = [p, C.c_int64, C.c_int32]
     lib.ist_oracle_block.restype = C.c_int32
     lib.ist_oracle_block.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p]
     for fn in (lib.ist_oracle_gather, lib.ist_oracle_scatter):
@@ -225,6 +227,47 @@ def subnet_sgd(Wl: List[np.ndarray], bl: Optional[List[Optional[np.ndarray]]], y
     if rc:
         raise ValueError("ist_oracle_subnet_sgd rejected its arguments")
     return loss
+
+
+def round_array(a: np.ndarray, mode: str) -> np.ndarray:
+    """Storage rounding of every element (a float64 copy)."""
+    out = np.array(a, dtype=np.float64, order="C", copy=True)
+    _load().ist_oracle_round_array(_ptr(out), out.size, MODE[mode])
+    return out
+
+
+def forward_full(Ws, bs, mode: str, X: Optional[np.ndarray] = None, csr=None,
+                 normalize: bool = False, eps: float = NORM_EPS) -> np.ndarray:
+    """Logits [B][N_t] of the full network of Section 2.1 on one batch, written out layer by
+    layer: f_l = ReLU(W_l f_{l-1} + b_l), logits = W_t f_{t-1} + b_t; with `normalize` the input of
+    every hidden neuron is standardised over the batch first (Section 2.2, biased variance).
+    float64 arithmetic; hidden activations (and the standardised inputs) are rounded to the
+    storage type where the device stores them, the logits are not.
+    X [B][N_0], or csr = (rowptr [B+1], colidx, vals)."""
+    t = len(Ws)
+    if csr is None:
+        f = np.asarray(X, dtype=np.float64)
+    else:
+        rp, ci, va = csr
+        B = len(rp) - 1
+        f = np.zeros((B, Ws[0].shape[1]))
+        for bi in range(B):
+            for p in range(int(rp[bi]), int(rp[bi + 1])):
+                f[bi, int(ci[p])] += float(va[p])
+    for l in range(1, t + 1):
+        z = f @ np.asarray(Ws[l - 1], dtype=np.float64).T
+        if bs is not None and bs[l - 1] is not None:
+            z = z + np.asarray(bs[l - 1], dtype=np.float64)[None, :]
+        if l == t:
+            return z
+        if normalize:
+            mu = z.mean(axis=0, keepdims=True)
+            var = ((z - mu) ** 2).mean(axis=0, keepdims=True)
+            z = round_array((z - mu) / np.sqrt(var + eps), mode)
+            f = np.maximum(z, 0.0)
+        else:
+            f = round_array(np.maximum(z, 0.0), mode)
+    raise AssertionError("unreachable")
 
 
 def csr_slice(rowptr, colidx, vals, r0: int, r1: int):

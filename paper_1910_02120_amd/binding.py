@@ -25,7 +25,8 @@ EXPORTS = ["ist_create", "ist_destroy", "ist_subnets_bytes", "ist_workspace_byte
            "ist_set_checked", "ist_partition", "ist_subnet_steps", "ist_merge", "ist_subnet_export",
            "ist_subnet_shape", "ist_last_error", "ist_version", "ist_profile_enable",
            "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name",
-           "ist_profile_kernel_count", "ist_profile_kernel", "ist_bind_spare", "ist_resample"]
+           "ist_profile_kernel_count", "ist_profile_kernel", "ist_bind_spare", "ist_resample",
+           "ist_forward_full"]
 
 
 class ISTError(RuntimeError):
@@ -72,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.ist_partition.argtypes = [p, C.POINTER(_Params), C.POINTER(p), p]
     lib.ist_subnet_steps.argtypes = [p, C.POINTER(_Batch), C.c_float, C.c_int32, p, p]
     lib.ist_merge.argtypes = [p, C.POINTER(_Params), p]
+    lib.ist_forward_full.argtypes = [p, C.POINTER(_Params), C.POINTER(_Batch), p, p]
     lib.ist_bind_spare.argtypes = [p, p, C.c_size_t]
     lib.ist_resample.argtypes = [p, C.POINTER(_Params), C.POINTER(p), p]
     lib.ist_subnet_export.argtypes = [p, C.c_int32, C.c_int32, p, p, p]
@@ -217,6 +219,32 @@ class ISTContext:
     def merge(self, Ws, bs, stream=None):
         pr = self._params(Ws, bs)
         self._check(self.lib.ist_merge(self._ctx, C.byref(pr), _stream_ptr(stream)))
+
+    def forward_full(self, Ws, bs, B: int, X: torch.Tensor = None, csr=None,
+                     logits: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        """Logits [B][N_t] (float32) of the full network on samples 0..B-1 of X (rows of N_0
+        values) or of csr = (rowptr, colidx, vals)."""
+        pr = self._params(Ws, bs)
+        bt = _Batch()
+        td = _torch_dtype(self.dtype)
+        if self.input == "csr":
+            rp, ci, va = csr
+            assert rp.dtype == torch.int32 and ci.dtype == torch.int32 and va.dtype == td
+            assert rp.is_cuda and ci.is_cuda and va.is_cuda
+            assert rp.numel() >= B + 1 and ci.numel() == va.numel()
+            bt.rowptr, bt.colidx, bt.vals, bt.nnz = rp.data_ptr(), ci.data_ptr(), va.data_ptr(), ci.numel()
+        else:
+            assert X.is_cuda and X.is_contiguous() and X.dtype == td
+            assert X.numel() >= B * self.dims[0]
+            bt.x = X.data_ptr()
+        bt.B = int(B)
+        if logits is None:
+            logits = torch.empty((B, self.dims[-1]), dtype=torch.float32, device=self.device)
+        assert logits.is_cuda and logits.is_contiguous() and logits.dtype == torch.float32
+        assert logits.numel() >= B * self.dims[-1]
+        self._check(self.lib.ist_forward_full(self._ctx, C.byref(pr), C.byref(bt), logits.data_ptr(),
+                                              _stream_ptr(stream)))
+        return logits
 
     def resample(self, Ws, bs, perms: List[torch.Tensor], stream=None):
         """merge(Ws, bs) followed by partition(Ws, bs, perms), in one pass over the weights.

@@ -569,6 +569,69 @@ ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, voi
     return IST_OK;
 }
 
+ist_status ist_forward_full(ist_ctx *ctx, const ist_params *params, const ist_batch *bt, float *logits, void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound) return fail(ctx, IST_ESTATE, "ist_forward_full: call ist_bind first");
+    if (!params || !params->W || !bt || !logits) return fail(ctx, IST_EINVAL, "ist_forward_full: null argument");
+    if (ctx->has_bias && !params->b) return fail(ctx, IST_EINVAL, "ist_forward_full: null bias list");
+    if (bt->B < 1 || bt->B > ctx->max_B) return fail(ctx, IST_ESHAPE, "ist_forward_full: B outside 1..max_B");
+    const bool csr = ctx->input == IST_CSR;
+    if (csr) {
+        if (!bt->rowptr || !bt->colidx || !bt->vals || bt->nnz < 0)
+            return fail(ctx, IST_EINVAL, "ist_forward_full: incomplete CSR batch");
+    } else if (!bt->x) {
+        return fail(ctx, IST_EINVAL, "ist_forward_full: null x");
+    }
+    const int t = ctx->t, S = ctx->S, B = bt->B, dt = ctx->dtype;
+    for (int l = 1; l <= t; ++l)
+        if (!params->W[l - 1] || (ctx->has_bias && !params->b[l - 1]))
+            return fail(ctx, IST_EINVAL, "ist_forward_full: null parameter array");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = ctx->workspace;
+    // One group of full width: the activation regions hold S subnets of max_B x ldr each, which is
+    // exactly room for max_B rows of S * ldr >= N_l values.
+    auto pitch = [&](int l) { return (int64_t)S * ctx->layer[l - 1].ldr; };
+    for (int l = 1; l <= t; ++l) {
+        const LayerPlan &L = ctx->layer[l - 1];
+        const void *bias = ctx->has_bias ? params->b[l - 1] : nullptr;
+        const bool nrm = ctx->normalize && l < t;
+        if (l == 1 && csr) {
+            CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, 0, 0, 1, B, L.N_in, L.N_out, pitch(1)};
+            IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, params->W[0], bias, ws + L.off_act,
+                                       nrm ? reinterpret_cast<float *>(ws + L.off_z) : nullptr, dt, st, true),
+                    "csr forward (full network)");
+        } else {
+            GemmArgs a{};
+            set_split(ctx, a);
+            if (l == 1) { a.A = bt->x; a.sam = L.N_in; }
+            else { a.A = ws + ctx->layer[l - 2].off_act; a.sam = pitch(l - 1); }
+            a.sak = 1; a.gA = 0;
+            a.B = params->W[l - 1]; a.sbn = L.N_in; a.sbk = 1; a.gB = 0;
+            a.M = B; a.N = (int32_t)L.N_out; a.K = (int32_t)L.N_in; a.G = 1;
+            a.bias = bias; a.gBias = 0;
+            if (l == t) { a.C = logits; a.ldc = L.N_out; }
+            else if (nrm) { a.C = ws + L.off_z; a.ldc = pitch(l); }
+            else { a.C = ws + L.off_act; a.ldc = pitch(l); }
+            a.gC = 0;
+            IST_RUN(KC_GEMM_FWD, launch_gemm(dt, (l == t || nrm) ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st),
+                    "forward gemm (full network)");
+        }
+        if (nrm)
+            IST_RUN(KC_NORM, launch_norm_forward(reinterpret_cast<const float *>(ws + L.off_z), ws + L.off_zh,
+                                ws + L.off_act, reinterpret_cast<float *>(ws + L.off_isg), 1, B, L.N_out, pitch(l),
+                                ctx->norm_eps, dt, st), "standardise (full network)");
+    }
+    // Rows of full width overlay the subnets' padded rows: where a subnet row has padding columns
+    // (R not a multiple of 8) they now hold values, and ist_subnet_steps relies on zeros there.
+    bool padded = false;
+    for (int l = 1; l <= t; ++l) padded = padded || ctx->layer[l - 1].ldr != ctx->layer[l - 1].R;
+    if (padded)
+        IST_RUN(KC_BIAS_COPY, launch_fill_zero(ws + ctx->layer[0].off_act, ctx->off_zeros - ctx->layer[0].off_act, st),
+                "clear workspace");
+    return IST_OK;
+}
+
 ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t k, float *loss_out,
                             void *stream)
 {

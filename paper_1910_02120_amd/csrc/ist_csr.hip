@@ -13,7 +13,9 @@
 
 namespace ist {
 
-template <typename D>
+// ROWMAJOR: Wt is an untransposed W_1 [w][N0] instead (the full network's first layer: one group,
+// strided weight reads - an evaluation path, not the training one).
+template <typename D, bool ROWMAJOR = false>
 __global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D::T *__restrict__ Wt,
                                                      const typename D::T *__restrict__ bias,
                                                      typename D::T *__restrict__ h, float *__restrict__ z_out)
@@ -32,7 +34,7 @@ __global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D
     for (int64_t p = p0; p < p1; ++p) {
         int32_t col = c.colidx[p];
         if (col < 0 || col >= c.N0) continue;
-        acc = fmaf(D::up(vals[p]), D::ld(Wg + (int64_t)col * c.w + q), acc);
+        acc = fmaf(D::up(vals[p]), D::ld(ROWMAJOR ? Wg + q * c.N0 + col : Wg + (int64_t)col * c.w + q), acc);
     }
     if (bias) acc += D::ld(bias + (int64_t)g * c.w + q);
     if (z_out) z_out[((int64_t)g * c.B + b) * c.ld + q] = acc;
@@ -44,6 +46,12 @@ __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x)
         p[i] = v;
+}
+
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st)
+{
+    if (bytes / 4 > 0) hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, st, static_cast<uint32_t *>(p), (int64_t)(bytes / 4), 0u);
+    return hipGetLastError();
 }
 
 // bitmap[g][col][b >> 5] |= 1 << (b & 31) for every non-zero (b, col) of group g
@@ -125,10 +133,19 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
 }
 
 hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out, int dtype,
-                              hipStream_t st)
+                              hipStream_t st, bool rowmajor)
 {
     int th = c.w >= 256 ? 256 : (c.w > 64 ? 128 : 64);
     dim3 grid((unsigned)((c.w + th - 1) / th), (unsigned)c.B, (unsigned)c.G);
+    if (rowmajor) {
+        if (dtype == IST_BF16)
+            hipLaunchKernelGGL((k_csr_forward<BF16, true>), grid, dim3(th), 0, st, c, (const uint16_t *)Wt,
+                               (const uint16_t *)bias, (uint16_t *)h, z_out);
+        else
+            hipLaunchKernelGGL((k_csr_forward<F32, true>), grid, dim3(th), 0, st, c, (const float *)Wt,
+                               (const float *)bias, (float *)h, z_out);
+        return hipGetLastError();
+    }
     if (dtype == IST_BF16)
         hipLaunchKernelGGL(k_csr_forward<BF16>, grid, dim3(th), 0, st, c, (const uint16_t *)Wt,
                            (const uint16_t *)bias, (uint16_t *)h, z_out);

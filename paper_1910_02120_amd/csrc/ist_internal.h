@@ -230,8 +230,11 @@ struct CsrArgs {
     int64_t ld;               // row pitch of h_1 / dz_1
 };
 // z_out != null: write the fp32 pre-activation there instead of ReLU(.) to h
+// zero fill by a kernel (safe to record into a HIP graph); bytes is rounded down to a multiple of 4
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
+// rowmajor: Wt is W_1 itself, [w][N0] (full-network evaluation), not the transposed subnet block
 hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out,
-                              int dtype, hipStream_t st);
+                              int dtype, hipStream_t st, bool rowmajor = false);
 hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_t *bitmap,
                              float lr, int dtype, hipStream_t st);
 
