@@ -62,6 +62,12 @@ typedef struct {
                               sigma = sqrt(var + norm_eps); the gradient flows through mu and sigma.  0: plain
                               ReLU network. */
     float norm_eps;        /* > 0; values <= 0 select 1e-5 */
+    const float *layer_scale; /* [host] t factors gamma_1..gamma_t (finite, > 0), or NULL for none.  Appendix A,
+                              equation (4): the subnet's product of layer l is multiplied by gamma_l,
+                              z_l = gamma_l (W_l f_{l-1}) + b_l, and so are the gradients that flow through it.
+                              The paper's factor is n^2 = S^2 where both sides of W_l are partitioned (each
+                              subnet's masked output is then an unbiased estimate of the full product);
+                              Section 2.2 drops it in favour of `normalize`.  Read by ist_create only. */
 } ist_model_desc;
 
 /* Full parameters, caller-owned. [host struct, device arrays] */
@@ -163,6 +169,7 @@ ist_status ist_resample(ist_ctx *ctx, const ist_params *params, const int32_t *c
  * Section 2.1 that the subnets are cut from and merged back into; with `normalize` set the
  * inputs of the hidden neurons are standardised with the statistics of this batch (Section 2.2:
  * after training, mu and sigma are computed with the full network over a subset of the data).
+ * The full network has no masks, so layer_scale does not apply to it.
  * For evaluation between rounds.  Uses samples 0..B-1 of `batch` (x rows or CSR rows 0..B-1;
  * y and the strides are ignored), B <= max_B.  logits: [device] float [B][N_t].  Same storage
  * and accumulation types as ist_subnet_steps.  Needs ist_bind only; it overwrites the workspace

@@ -177,11 +177,35 @@ int32_t ist_oracle_subnet_sgd(int32_t t, const int64_t *n, double **W, double **
  * Storage rounding (mode 1/2): zh and dzh and dz are rounded where they are stored;
  * z, mu, sigma are not.
  */
+int32_t ist_oracle_subnet_sgd_scaled(int32_t t, const int64_t *n, double **W, double **b,
+                                     int32_t is_csr, const double *X, const int32_t *rowptr,
+                                     const int32_t *colidx, const double *vals, const int32_t *y,
+                                     int32_t B, int32_t k, double lr, int32_t mode, int32_t normalize,
+                                     double eps, const double *scale, double *loss_out);
+
 int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, double **b,
                                    int32_t is_csr, const double *X, const int32_t *rowptr,
                                    const int32_t *colidx, const double *vals, const int32_t *y,
                                    int32_t B, int32_t k, double lr, int32_t mode, int32_t normalize,
                                    double eps, double *loss_out)
+{
+    return ist_oracle_subnet_sgd_scaled(t, n, W, b, is_csr, X, rowptr, colidx, vals, y, B, k, lr, mode, normalize,
+                                        eps, NULL, loss_out);
+}
+
+/*
+ * The same with the subnet forward pass of Appendix A, equation (4): the product of layer l is
+ * multiplied by a factor gamma_l = scale[l-1] (the paper's n^2, which makes the sum over subnets
+ * of the masked products an unbiased estimate of W_l f_{l-1}),
+ *     z_l = gamma_l * (W_l h_{l-1}) + b_l,
+ * hence dh_{l-1} = gamma_l * (dz_l W_l) and dW_l = gamma_l * dz_l^T h_{l-1}; the bias is not
+ * scaled.  scale == NULL: every gamma_l = 1.
+ */
+int32_t ist_oracle_subnet_sgd_scaled(int32_t t, const int64_t *n, double **W, double **b,
+                                     int32_t is_csr, const double *X, const int32_t *rowptr,
+                                     const int32_t *colidx, const double *vals, const int32_t *y,
+                                     int32_t B, int32_t k, double lr, int32_t mode, int32_t normalize,
+                                     double eps, const double *scale, double *loss_out)
 {
     if (t < 1 || B <= 0 || k < 0) return -1;
     double **zh = (double **)calloc((size_t)t + 1, sizeof(double *));
@@ -225,6 +249,7 @@ int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, doub
 #pragma omp simd reduction(+ : acc)
                     for (int64_t c = 0; c < nin; ++c) acc += hr[c] * wr[c];
                 }
+                if (scale) acc *= scale[l - 1];
                 if (bl) acc += bl[r];
                 if (l < t && !normalize) acc = round_store(acc > 0.0 ? acc : 0.0, mode);
                 hout[bi * nout + r] = acc; /* logits (and inputs of the standardisation) stay unrounded */
@@ -296,6 +321,8 @@ int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, doub
 #pragma omp simd
                         for (int64_t c = 0; c < nin; ++c) row[c] += gv * wr[c];
                     }
+                    if (scale)
+                        for (int64_t c = 0; c < nin; ++c) row[c] *= scale[l - 1];
                     for (int64_t c = 0; c < nin; ++c)
                         row[c] = round_store(hprev[bi * nin + c] > 0.0 ? row[c] : 0.0, mode);
                 }
@@ -318,7 +345,8 @@ int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, doub
                 }
             }
 
-            /* dW_l = dz_l^T h_{l-1};  W_l <- W_l - lr dW_l;  b_l <- b_l - lr sum_b dz_l */
+            /* dW_l = gamma_l dz_l^T h_{l-1};  W_l <- W_l - lr dW_l;  b_l <- b_l - lr sum_b dz_l */
+            const double gam = scale ? scale[l - 1] : 1.0;
 #pragma omp parallel
             {
                 double *dwrow = (double *)calloc((size_t)nin, sizeof(double));
@@ -338,7 +366,7 @@ int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, doub
                             for (int32_t p = rp[bi]; p < rp[bi + 1]; ++p) {
                                 int32_t c = colidx[p];
                                 if (dwrow[c] != 0.0) {
-                                    wr[c] = round_store(wr[c] - lr * dwrow[c], mode);
+                                    wr[c] = round_store(wr[c] - lr * (gam * dwrow[c]), mode);
                                     dwrow[c] = 0.0;
                                 }
                             }
@@ -353,7 +381,7 @@ int32_t ist_oracle_subnet_sgd_norm(int32_t t, const int64_t *n, double **W, doub
                             for (int64_t c = 0; c < nin; ++c) dwrow[c] += gv * hr[c];
                         }
                         for (int64_t c = 0; c < nin; ++c)
-                            wr[c] = round_store(wr[c] - lr * dwrow[c], mode);
+                            wr[c] = round_store(wr[c] - lr * (gam * dwrow[c]), mode);
                     }
                     if (bl) bl[r] = round_store(bl[r] - lr * db, mode);
                 }

@@ -75,6 +75,10 @@ def _load():
     lib.ist_oracle_subnet_sgd_norm.argtypes = [C.c_int32, p, p, p, C.c_int32, p, p, p, p, p,
                                                C.c_int32, C.c_int32, C.c_double, C.c_int32, C.c_int32,
                                                C.c_double, p]
+    lib.ist_oracle_subnet_sgd_scaled.restype = C.c_int32
+    lib.ist_oracle_subnet_sgd_scaled.argtypes = [C.c_int32, p, p, p, C.c_int32, p, p, p, p, p,
+                                                 C.c_int32, C.c_int32, C.c_double, C.c_int32, C.c_int32,
+                                                 C.c_double, p, p]
     lib.ist_oracle_subnet_sgd.restype = C.c_int32
     lib.ist_oracle_subnet_sgd.argtypes = [C.c_int32, p, p, p, C.c_int32, p, p, p, p, p,
                                           C.c_int32, C.c_int32, C.c_double, C.c_int32, p]
@@ -188,10 +192,11 @@ NORM_EPS = 1e-5   # epsilon under the square root of the per-neuron standardisat
 
 def subnet_sgd(Wl: List[np.ndarray], bl: Optional[List[Optional[np.ndarray]]], y: np.ndarray,
                lr: float, k: int, mode: str, X: Optional[np.ndarray] = None, csr=None,
-               normalize: bool = False, eps: float = NORM_EPS):
+               normalize: bool = False, eps: float = NORM_EPS, scale=None):
     """k local SGD steps on one subnet.  Wl/bl are float64 arrays updated in place.
     X: [k][B][n_0] float64, or csr = (rowptr[k*B+1], colidx, vals float64).
     normalize: standardise every hidden neuron's input over the mini-batch (Section 2.2).
+    scale: factors gamma_l of the layer products (Appendix A, equation (4): n^2), None = 1.
     Returns loss[k]."""
     t = len(Wl)
     for w in Wl:
@@ -221,9 +226,11 @@ def subnet_sgd(Wl: List[np.ndarray], bl: Optional[List[Optional[np.ndarray]]], y
         assert rp.shape[0] == k * B + 1
         assert ci.size == 0 or (ci.min() >= 0 and ci.max() < n[0])
         args = (1, None, _ptr(rp), _ptr(ci), _ptr(va))
-    rc = _load().ist_oracle_subnet_sgd_norm(t, _ptr(n), Wp, bp, *args, _ptr(y), B, k,
-                                            float(np.float32(lr)), MODE[mode], 1 if normalize else 0,
-                                            float(eps), _ptr(loss))
+    sc = None if scale is None else np.ascontiguousarray(scale, dtype=np.float64)
+    assert sc is None or sc.shape == (t,)
+    rc = _load().ist_oracle_subnet_sgd_scaled(t, _ptr(n), Wp, bp, *args, _ptr(y), B, k,
+                                              float(np.float32(lr)), MODE[mode], 1 if normalize else 0,
+                                              float(eps), _ptr(sc), _ptr(loss))
     if rc:
         raise ValueError("ist_oracle_subnet_sgd rejected its arguments")
     return loss
@@ -237,13 +244,15 @@ def round_array(a: np.ndarray, mode: str) -> np.ndarray:
 
 
 def forward_full(Ws, bs, mode: str, X: Optional[np.ndarray] = None, csr=None,
-                 normalize: bool = False, eps: float = NORM_EPS) -> np.ndarray:
+                 normalize: bool = False, eps: float = NORM_EPS, scale=None) -> np.ndarray:
     """Logits [B][N_t] of the full network of Section 2.1 on one batch, written out layer by
     layer: f_l = ReLU(W_l f_{l-1} + b_l), logits = W_t f_{t-1} + b_t; with `normalize` the input of
     every hidden neuron is standardised over the batch first (Section 2.2, biased variance).
     float64 arithmetic; hidden activations (and the standardised inputs) are rounded to the
     storage type where the device stores them, the logits are not.
-    X [B][N_0], or csr = (rowptr [B+1], colidx, vals)."""
+    X [B][N_0], or csr = (rowptr [B+1], colidx, vals).  scale: factors gamma_l applied to the
+    products W_l f_{l-1} (a subnet's forward pass in Appendix A, equation (4)); None for the full
+    network, which has none."""
     t = len(Ws)
     if csr is None:
         f = np.asarray(X, dtype=np.float64)
@@ -256,6 +265,8 @@ def forward_full(Ws, bs, mode: str, X: Optional[np.ndarray] = None, csr=None,
                 f[bi, int(ci[p])] += float(va[p])
     for l in range(1, t + 1):
         z = f @ np.asarray(Ws[l - 1], dtype=np.float64).T
+        if scale is not None:
+            z = float(scale[l - 1]) * z
         if bs is not None and bs[l - 1] is not None:
             z = z + np.asarray(bs[l - 1], dtype=np.float64)[None, :]
         if l == t:
@@ -277,7 +288,7 @@ def csr_slice(rowptr, colidx, vals, r0: int, r1: int):
 
 
 def subnet_steps(subs_f64, lr: float, k: int, mode: str, y: np.ndarray,
-                 X: Optional[np.ndarray] = None, csr=None, normalize: bool = False):
+                 X: Optional[np.ndarray] = None, csr=None, normalize: bool = False, scale=None):
     """Local SGD on every subnet independently (no communication between them).
     subs_f64[s] = (W list, b list) in float64, updated in place; X [S][k][B][N_0]
     or a CSR whose row (s*k + j)*B + b is sample b of step j of subnet s.
@@ -288,9 +299,9 @@ def subnet_steps(subs_f64, lr: float, k: int, mode: str, y: np.ndarray,
     for s in range(S):
         Wl, bl = subs_f64[s]
         if csr is None:
-            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, X=X[s, :k], normalize=normalize)
+            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, X=X[s, :k], normalize=normalize, scale=scale)
         else:
-            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, normalize=normalize,
+            losses[s] = subnet_sgd(Wl, bl, y[s, :k], lr, k, mode, normalize=normalize, scale=scale,
                                    csr=csr_slice(*csr, s * y.shape[1] * B, (s * y.shape[1] + k) * B))
     return losses
 

@@ -38,7 +38,8 @@ class ISTError(RuntimeError):
 class _ModelDesc(C.Structure):
     _fields_ = [("t", C.c_int32), ("dims", C.POINTER(C.c_int64)), ("S", C.c_int32),
                 ("dtype", C.c_int32), ("input", C.c_int32), ("has_bias", C.c_int32),
-                ("normalize", C.c_int32), ("norm_eps", C.c_float)]
+                ("normalize", C.c_int32), ("norm_eps", C.c_float),
+                ("layer_scale", C.POINTER(C.c_float))]
 
 
 class _Params(C.Structure):
@@ -113,7 +114,8 @@ class ISTContext:
 
     def __init__(self, dims: Sequence[int], S: int, dtype: str = "f32", input: str = "dense",
                  has_bias: bool = True, max_B: int = 128, device: str = "cuda:0",
-                 bind: bool = True, normalize: bool = False, norm_eps: float = 0.0):
+                 bind: bool = True, normalize: bool = False, norm_eps: float = 0.0,
+                 layer_scale: Optional[Sequence[float]] = None):
         self.lib = load_library()
         self.dims = [int(d) for d in dims]
         self.t = len(self.dims) - 1
@@ -123,6 +125,10 @@ class ISTContext:
         desc = _ModelDesc(self.t, self._dims_arr, self.S, IST_BF16 if dtype == "bf16" else IST_F32,
                           IST_CSR if input == "csr" else IST_DENSE, 1 if has_bias else 0,
                           1 if normalize else 0, float(norm_eps))
+        if layer_scale is not None:
+            assert len(layer_scale) == self.t
+            self._scale_arr = (C.c_float * self.t)(*[float(v) for v in layer_scale])
+            desc.layer_scale = self._scale_arr
         self.normalize = bool(normalize)
         self._ctx = C.c_void_p()
         st = self.lib.ist_create(C.byref(desc), int(max_B), C.byref(self._ctx))

@@ -143,6 +143,9 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         (d->input != IST_DENSE && d->input != IST_CSR) || (d->has_bias != 0 && d->has_bias != 1) ||
         (d->normalize != 0 && d->normalize != 1) || !(d->norm_eps == d->norm_eps))
         return IST_EINVAL;
+    if (d->layer_scale)
+        for (int l = 0; l < d->t; ++l)
+            if (!(d->layer_scale[l] > 0.0f) || !(d->layer_scale[l] <= 3.0e38f)) return IST_EINVAL;
     if (max_B < 1) return IST_ESHAPE;
     if (d->S > 4096) return IST_EUNSUPPORTED;   // the output-bias mean is a two-level tree of 64
     for (int l = 0; l <= d->t; ++l) {
@@ -155,6 +158,8 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     ctx->has_bias = d->has_bias; ctx->max_B = max_B;
     ctx->normalize = d->normalize; ctx->norm_eps = d->norm_eps > 0.0f ? d->norm_eps : 1e-5f;
     ctx->dims.assign(d->dims, d->dims + d->t + 1);
+    ctx->scale.assign((size_t)d->t, 1.0f);
+    if (d->layer_scale) ctx->scale.assign(d->layer_scale, d->layer_scale + d->t);
     const int t = d->t, S = d->S, e = ctx->esz();
 
     // ---- subnet buffer: index tables, then per-layer blocks and biases ----
@@ -665,6 +670,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             const void *bias = ctx->has_bias ? sb + L.off_b : nullptr;
             if (l == 1 && csr) {
                 CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R, L.ldr};
+                c.alpha = ctx->scale[0];
                 const bool nrm = ctx->normalize && l < t;
                 IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, sb + L.off_W, bias, ws + L.off_act,
                                            nrm ? reinterpret_cast<float *>(ws + L.off_z) : nullptr, dt, st), "csr forward");
@@ -688,6 +694,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             a.C = ws + L.off_act; a.ldc = L.ldr; a.gC = (int64_t)B * L.ldr;
             a.M = B; a.N = (int32_t)L.R; a.K = (int32_t)L.C; a.G = S;
             a.bias = bias; a.gBias = L.R;
+            a.alpha = ctx->scale[l - 1];
             if (l == t && ctx->fused_out) {
                 // pass 1: per-row, per-column-block max / sum(exp); pass 2 (after the row
                 // statistics are combined): recompute the logits and store dz_t directly
@@ -735,7 +742,8 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 const int64_t mn = (int64_t)B * L.R;
                 IST_RUN(KC_SOFTMAX_XENT, launch_xent_rows(reinterpret_cast<const float *>(ws + ctx->off_partial), out_splits, mn,
                                             out_splits * mn, L.R, ctx->has_bias ? sb + L.off_b : nullptr, L.R, bt->y + row0,
-                                            bt->stride_s, ws + L.off_dz, L.ldr, rowloss, S, B, (int32_t)L.R, dt, st),
+                                            bt->stride_s, ws + L.off_dz, L.ldr, rowloss, S, B, (int32_t)L.R, dt, st,
+                                            ctx->scale[t - 1]),
                         "softmax cross-entropy (from partial products)");
             } else {
                 IST_RUN(KC_SOFTMAX_XENT, launch_xent_rows(reinterpret_cast<const float *>(ws + L.off_act), 1, 0,
@@ -761,6 +769,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.C = ws + P.off_dz; a.ldc = P.ldr; a.gC = (int64_t)B * P.ldr;
                 a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
                 a.mask = ws + P.off_act; a.ldm = P.ldr; a.gMask = (int64_t)B * P.ldr;
+                a.alpha = ctx->scale[l - 1];
                 IST_RUN(KC_GEMM_BWD_DATA, launch_gemm(dt, EPI_BWD_DATA, a, st), "backward-data gemm");
                 if (ctx->normalize)   // what the product left is d loss / d zh_{l-1}: back through the standardisation
                     IST_RUN(KC_NORM, launch_norm_backward(ws + P.off_dz, ws + P.off_zh,
@@ -770,7 +779,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             if (l == 1 && csr) {
                 CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, row0, bt->stride_s, S, B, L.C, L.R, L.ldr};
                 IST_RUN(KC_CSR_UPDATE, launch_csr_update(c, sb + L.off_W, ws + L.off_dz,
-                                          reinterpret_cast<uint32_t *>(ws + ctx->off_bitmap), lr, dt, st),
+                                          reinterpret_cast<uint32_t *>(ws + ctx->off_bitmap), lr * ctx->scale[0], dt, st),
                         "csr update");
             } else {       // W_l <- W_l - lr * dz_l^T h_{l-1}
                 GemmArgs a{};
@@ -786,7 +795,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.sbn = 1; a.sbk = (l == 1) ? L.C : ctx->layer[l - 2].ldr;
                 a.C = sb + L.off_W; a.ldc = L.C; a.gC = L.R * L.C;
                 a.M = (int32_t)L.R; a.N = (int32_t)L.C; a.K = B; a.G = S;
-                a.lr = lr;
+                a.lr = lr * ctx->scale[l - 1];   // dW_l = gamma_l dz_l^T h_{l-1}
                 IST_RUN(KC_GEMM_UPDATE, launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
             }
         }

@@ -36,6 +36,7 @@ __global__ __launch_bounds__(256) void k_csr_forward(CsrArgs c, const typename D
         if (col < 0 || col >= c.N0) continue;
         acc = fmaf(D::up(vals[p]), D::ld(ROWMAJOR ? Wg + q * c.N0 + col : Wg + (int64_t)col * c.w + q), acc);
     }
+    acc *= c.alpha;
     if (bias) acc += D::ld(bias + (int64_t)g * c.w + q);
     if (z_out) z_out[((int64_t)g * c.B + b) * c.ld + q] = acc;
     else h[((int64_t)g * c.B + b) * c.ld + q] = D::cvt(acc > 0.0f ? acc : 0.0f);

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void k_gemm_generic(GemmArgs a)
         for (int j = 0; j < 4; ++j) {
             int n = n0 + tx * 4 + j;
             if (n >= a.N) continue;
-            float v = acc[i][j];
+            float v = EPI == EPI_UPDATE ? acc[i][j] : a.alpha * acc[i][j];
             int64_t ci = (int64_t)g * a.gC + (int64_t)m * a.ldc + n;
             if (EPI == EPI_FWD_RELU) {
                 if (a.bias) v += D::ld(static_cast<const T *>(a.bias) + (int64_t)g * a.gBias + n);

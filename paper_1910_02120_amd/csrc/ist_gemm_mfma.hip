@@ -272,7 +272,7 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
     }
     if (EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) val[i] += bias8[i];
+        for (int i = 0; i < 8; ++i) val[i] = fmaf(a.alpha, val[i], bias8[i]);   // alpha = 1: exactly val + bias
         if (EPI == EPI_FWD_RELU) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) val[i] = val[i] > 0.0f ? val[i] : 0.0f;
@@ -287,7 +287,7 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
         if (HASPRE && vec) pre8_decode<T>(pre, o);
         else Row8<T>::ld(static_cast<const T *>(a.mask) + (int64_t)g * a.gMask + (int64_t)m * a.ldm + n0, vec, nv, o);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) val[i] = o[i] > 0.0f ? val[i] : 0.0f;
+        for (int i = 0; i < 8; ++i) val[i] = o[i] > 0.0f ? a.alpha * val[i] : 0.0f;
     } else {   // EPI_UPDATE
         if (HASPRE && vec) pre8_decode<T>(pre, o);
         else Row8<T>::ld(static_cast<const T *>(a.C) + ci, vec, nv, o);
@@ -307,7 +307,7 @@ __device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk,
     const bool rowok = m < a.M;
     const int nv = !rowok ? 0 : (a.N - n0 >= 8 ? 8 : (a.N - n0 > 0 ? a.N - n0 : 0));
 #pragma unroll
-    for (int i = 0; i < 8; ++i) val[i] += bias8[i];
+    for (int i = 0; i < 8; ++i) val[i] = fmaf(a.alpha, val[i], bias8[i]);
     // exp(x) = exp2(x * log2(e)): scale once, then only v_exp_f32 per element
     constexpr float kLog2e = 1.4426950408889634f;
     float mx = -INFINITY, se = 0.0f;
@@ -352,7 +352,7 @@ __device__ inline void epi_dz(const GemmArgs &a, int g, int m, int n0, float (&v
     const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
     const bool vec = vecC && nv == 8;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) val[i] += bias8[i];
+    for (int i = 0; i < 8; ++i) val[i] = fmaf(a.alpha, val[i], bias8[i]);
     constexpr float kLog2e = 1.4426950408889634f;
     const float ls = lse * kLog2e;
 #pragma unroll

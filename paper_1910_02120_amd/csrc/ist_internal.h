@@ -77,6 +77,7 @@ struct ist_ctx {
     int32_t t = 0, S = 0, dtype = 0, input = 0, has_bias = 0, max_B = 0, normalize = 0;
     float norm_eps = 1e-5f;
     std::vector<int64_t> dims;
+    std::vector<float> scale;             // index l-1: factor of the product of layer l (1 without layer_scale)
     std::vector<ist::LayerPlan> layer;    // index l-1
     std::vector<ist::HiddenPlan> hidden;  // index l-1, l = 1..t-1
     size_t subnets_bytes = 0, workspace_bytes = 0;
@@ -168,6 +169,7 @@ struct GemmArgs {
     const void *bias; int64_t gBias;          // EPI_FWD_*: bias[n] (may be null)
     const void *mask; int64_t ldm, gMask;     // EPI_BWD_DATA: keep where mask[m][n] > 0
     float lr;                                 // EPI_UPDATE: C = C - lr * acc
+    float alpha = 1.0f;                       // forward: alpha * acc + bias; backward-data: alpha * acc (layer factor)
     float *partial; size_t partial_bytes;     // split-K scratch (fp32 partial products), may be null
     int32_t keep_partial;                     // host flag: a k-split launch leaves the partial products unfinished
     const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
@@ -203,7 +205,8 @@ hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_
 constexpr int kXentRowsMaxC = 256;
 hipError_t launch_xent_rows(const float *z, int32_t splits, int64_t split_stride, int64_t g_stride, int64_t ldz,
                             const void *bias, int64_t gBias, const int32_t *y, int64_t y_stride_g, void *dz,
-                            int64_t ld, float *rowloss, int32_t G, int32_t B, int32_t Cn, int dtype, hipStream_t st);
+                            int64_t ld, float *rowloss, int32_t G, int32_t B, int32_t Cn, int dtype, hipStream_t st,
+                            float alpha = 1.0f /* factor of the summed partial products, before the bias */);
 // row losses of up to this many steps wait in the workspace for one reduction launch
 constexpr int kLossSlots = 16;
 // Section 2.2 standardisation of hidden-neuron inputs over the mini-batch, per subnet g and column r:
@@ -228,6 +231,7 @@ struct CsrArgs {
     int64_t row0, stride_g;   // sample b of group g is CSR row row0 + g*stride_g + b
     int32_t G, B; int64_t N0, w;
     int64_t ld;               // row pitch of h_1 / dz_1
+    float alpha = 1.0f;       // forward: alpha * (x W^T) + bias (layer factor)
 };
 // z_out != null: write the fp32 pre-activation there instead of ReLU(.) to h
 // zero fill by a kernel (safe to record into a HIP graph); bytes is rounded down to a multiple of 4

@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void k_xent_rows(const float *__restrict__ z, 
                                                    const typename D::T *__restrict__ bias, int64_t gBias,
                                                    const int32_t *__restrict__ y, int64_t y_stride_g,
                                                    typename D::T *__restrict__ dz, int64_t ld,
-                                                   float *__restrict__ rowloss, int32_t G, int32_t B, int32_t Cn)
+                                                   float *__restrict__ rowloss, int32_t G, int32_t B, int32_t Cn,
+                                                   float alpha)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -112,6 +113,7 @@ __global__ __launch_bounds__(256) void k_xent_rows(const float *__restrict__ z, 
         if (c < Cn) {
 #pragma unroll 8
             for (int sp = 0; sp < splits; ++sp) acc += zr[(int64_t)sp * split_stride + c];
+            acc *= alpha;
             if (bias) acc += D::ld(bias + (int64_t)g * gBias + c);
         }
         v[i] = c < Cn ? acc : -INFINITY;
@@ -140,18 +142,19 @@ __global__ __launch_bounds__(256) void k_xent_rows(const float *__restrict__ z, 
 
 hipError_t launch_xent_rows(const float *z, int32_t splits, int64_t split_stride, int64_t g_stride, int64_t ldz,
                             const void *bias, int64_t gBias, const int32_t *y, int64_t y_stride_g, void *dz,
-                            int64_t ld, float *rowloss, int32_t G, int32_t B, int32_t Cn, int dtype, hipStream_t st)
+                            int64_t ld, float *rowloss, int32_t G, int32_t B, int32_t Cn, int dtype, hipStream_t st,
+                            float alpha)
 {
     if (Cn > 256 || splits < 1) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(((int64_t)G * B + 3) / 4));
     if (dtype == IST_BF16)
         hipLaunchKernelGGL((k_xent_rows<BF16>), grid, dim3(256), 0, st, z, splits, split_stride, g_stride, ldz,
                            static_cast<const uint16_t *>(bias), gBias, y, y_stride_g, static_cast<uint16_t *>(dz), ld,
-                           rowloss, G, B, Cn);
+                           rowloss, G, B, Cn, alpha);
     else
         hipLaunchKernelGGL((k_xent_rows<F32>), grid, dim3(256), 0, st, z, splits, split_stride, g_stride, ldz,
                            static_cast<const float *>(bias), gBias, y, y_stride_g, static_cast<float *>(dz), ld,
-                           rowloss, G, B, Cn);
+                           rowloss, G, B, Cn, alpha);
     return hipGetLastError();
 }
 

@@ -46,8 +46,9 @@ class Problem:
     """Seeded inputs of one configuration on the host and on the device."""
 
     def __init__(self, cfg: gen.ISTConfig, rnd: int = 0, bias_scale: float = 0.05, has_bias=True,
-                 dev="cuda:0", normalize=False):
+                 dev="cuda:0", normalize=False, scale=None):
         self.cfg, self.dev, self.has_bias, self.normalize = cfg, dev, has_bias, normalize
+        self.scale = None if scale is None else [float(np.float32(v)) for v in scale]   # factors of Appendix A
         self.Ws, self.bs = gen.make_weights(cfg, with_bias=has_bias, bias_scale=bias_scale)
         self.perms = gen.make_perms(cfg, rnd)
         if cfg.input == "csr":
@@ -75,7 +76,7 @@ class Problem:
         from paper_1910_02120_amd import ISTContext
         cfg = self.cfg
         return ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, self.has_bias, max_B=cfg.B,
-                          device=self.dev, normalize=self.normalize)
+                          device=self.dev, normalize=self.normalize, layer_scale=self.scale)
 
     def gpu_steps(self, ctx, k=None, loss=True):
         cfg = self.cfg
@@ -95,9 +96,9 @@ class Problem:
         k = cfg.k if k is None else k
         mode = cfg.dtype if mode is None else mode
         if cfg.input == "csr":
-            return orc.subnet_steps(subs, cfg.lr, k, mode, self.y, normalize=self.normalize,
+            return orc.subnet_steps(subs, cfg.lr, k, mode, self.y, normalize=self.normalize, scale=self.scale,
                                     csr=(self.rp, self.ci, self.va.astype(np.float64)))
-        return orc.subnet_steps(subs, cfg.lr, k, mode, self.y, X=self.X, normalize=self.normalize)
+        return orc.subnet_steps(subs, cfg.lr, k, mode, self.y, X=self.X, normalize=self.normalize, scale=self.scale)
 
 
 def export_all(ctx, cfg):

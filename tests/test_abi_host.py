@@ -83,3 +83,17 @@ def test_create_validates_the_normalisation_fields(lib):
     ctx = C.c_void_p()
     assert lib.ist_create(C.byref(_ModelDesc(3, arr, 4, 0, 0, 1, 2, 0.0)), 8, C.byref(ctx)) == -1
     assert lib.ist_create(C.byref(_ModelDesc(3, arr, 4, 0, 0, 1, 1, float("nan"))), 8, C.byref(ctx)) == -1
+
+
+def test_create_validates_the_layer_factors(lib):
+    from paper_1910_02120_amd.binding import _ModelDesc
+    dims = [8, 16, 16, 4]
+    arr = (C.c_int64 * len(dims))(*dims)
+    for vals, want in (((1.0, 16.0, 1.0), 0), ((1.0, 0.0, 1.0), -1), ((1.0, -4.0, 1.0), -1),
+                       ((float("nan"), 1.0, 1.0), -1), ((1.0, 1.0, float("inf")), -1)):
+        sc = (C.c_float * 3)(*vals)
+        d = _ModelDesc(3, arr, 4, 0, 0, 1, 0, 0.0, sc)
+        ctx = C.c_void_p()
+        assert lib.ist_create(C.byref(d), 8, C.byref(ctx)) == want, vals
+        if want == 0:
+            assert lib.ist_destroy(ctx) == 0

@@ -306,6 +306,38 @@ def test_k_local_steps_with_standardisation_match_oracle(name):
     ctx.close()
 
 
+def _factors(cfg, paper):
+    """Layer factors of Appendix A, equation (4).  paper: n^2 on the layers with both sides partitioned,
+    1 elsewhere; otherwise moderate factors on every layer, so that the first (dense or sparse) and the
+    output layer (stored logits, partial products, two-pass cross-entropy) take theirs too."""
+    if paper:
+        return [float(cfg.S ** 2) if 1 < l < cfg.t else 1.0 for l in range(1, cfg.t + 1)]
+    return [1.5 if l == 1 else (0.5 if l == cfg.t else 2.0) for l in range(1, cfg.t + 1)]
+
+
+@pytest.mark.parametrize("name,paper,normalize", [
+    ("cfg1", True, False), ("cfg1", False, False), ("ragged-f32", False, False), ("ragged-bf16", False, False),
+    ("cfg3-small", False, False), ("cfg4-small", False, False), ("cfg5-small", False, False),
+    ("csr-f32", False, False), ("wide-out-f32", False, False), ("many-steps-f32", False, False),
+    ("mid-out-bf16", False, False), ("deep-bf16", False, False), ("speech-small", False, False),
+    ("cfg4-small", True, True), ("ragged-f32", False, True), ("cfg5-small", False, True)])
+def test_k_local_steps_with_layer_factors_match_oracle(name, paper, normalize):
+    """Appendix A, equation (4): the product of layer l multiplied by gamma_l in the forward pass, hence in
+    both gradients.  With the standardisation the factor of a hidden layer only matters through epsilon."""
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, dev=_dev(), normalize=normalize, scale=_factors(cfg, paper))
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    loss = P.gpu_steps(ctx)
+    subs = P.oracle_subnets()
+    want_loss = P.oracle_steps(subs)
+    tol = H.TOL[cfg.dtype]
+    worst = H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, tol)
+    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
+    print(f"{name} (factors {P.scale}): worst parameter rel err {worst:.3e} (tol {tol})")
+    ctx.close()
+
+
 @pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "cfg5-small",
                                   "csr-f32", "wide-out-f32", "deep-bf16", "width-one-blocks-f32", "cfg1-nobias-S1"])
 def test_resample_equals_merge_then_partition(name):
