@@ -594,6 +594,73 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
             prologue();              // a branch around loads would force the loop to drain them
         }
 
+        if constexpr (EPI == EPI_LSE) {
+            // ---- row statistics straight from the accumulators ----
+            // Per 32x32 block a lane holds 16 values of ONE row (lane % 32): columns 8 (v / 4) +
+            // 4 (lane / 32) + v % 4; lane ^ 32 holds the other 16.  Max and sum(exp) over the wave's
+            // 32 TN columns are in-lane reductions plus one cross-lane step: no staging, no stores
+            // of logits.  The bias of the block tile's columns goes through LDS as floats (the
+            // operand tiles are free after the last barrier of the k-loop).
+            using T = typename D::T;
+            for (int c = threadIdx.x; c < BN; c += NT) {
+                const int n = cn0 + c;
+                fsm[c] = (a.bias && n < a.N) ? D::ld(static_cast<const T *>(a.bias) + (int64_t)cg * a.gBias + n) : 0.0f;
+            }
+            __syncthreads();
+            const int ncol0 = cn0 + wn;   // first column of the wave tile
+            if (kg == 0 && ncol0 < a.N) {
+                constexpr float kLog2e = 1.4426950408889634f;
+                const int half = lane >> 5, r32 = lane & 31;
+                const bool full = ncol0 + 32 * TN <= a.N;
+                const int blk = ncol0 / (32 * TN);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int m = cm0 + wm + 32 * i + r32;
+                    const int label = m < a.M ? a.y[(int64_t)cg * a.gY + m] : -1;
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int c = wn + 32 * j + 8 * q + 4 * half;
+                            const float4 b4 = *reinterpret_cast<const float4 *>(fsm + c);
+                            const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                float z = fmaf(a.alpha, acc[i][j][4 * q + u], bb[u]);
+                                if (!full) z = (cn0 + c + u < a.N) ? z : -INFINITY;
+                                acc[i][j][4 * q + u] = z;
+                                mx = fmaxf(mx, z);
+                            }
+                        }
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float ms = mx * kLog2e;
+                    float se = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) se += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], kLog2e, -ms));
+                    se += __shfl_xor(se, 32);
+                    if (m < a.M && half == 0 && blk < a.nb) {
+                        const int64_t pi = ((int64_t)cg * a.nb + blk) * a.M + m;   // [g][block][row]: rows are the fast index
+                        a.pmax[pi] = mx;
+                        a.psum[pi] = se;
+                    }
+                    // the logit of the label: rare (one block per row), so behind a wave-uniform test
+                    const int rel = label - ncol0;
+                    const bool hit = rel >= 0 && rel < 32 * TN && ((rel >> 2) & 1) == half;
+                    if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+                        float zl = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v)
+                                zl = (32 * j + 8 * (v / 4) + 4 * half + v % 4 == rel) ? acc[i][j][v] : zl;
+                        if (hit) a.zlabel[(int64_t)cg * a.M + m] = zl;
+                    }
+                }
+            }
+        } else {
         // ---- epilogue through LDS: each lane gets 8 consecutive columns of one row ----
         float *stage = fsm + w4 * (32 * LDC);
         constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
@@ -684,6 +751,7 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
             }
             if (PRE && i + PD < TM) preload(i + PD, pre[i % PD]);
         }
+        }
         if (!more) break;
         t = tn;
         __syncthreads();   // staging reads are done before the next tile's LDS stores
@@ -764,7 +832,17 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
     p.tile = 64;
     p.tiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * G;
     int splits = 1;
-    if (allow_split && p.tiles <= 256 && K >= 16384) {
+    if (allow_split && esz == 2 && K >= 16384 && M > 128 && M <= 256 && N <= 128) {
+        // a very long k over an output of at most one 256x128 block per group (backward-data of a wide
+        // output layer): one block covers the whole output, so every operand byte is fetched once -
+        // 64x64 blocks on different XCDs re-read dz twice and W four times
+        p.cover = 1;
+        p.tiles = G;
+        const int64_t want = 1024 / p.tiles > 0 ? 1024 / p.tiles : 1;
+        const int64_t most = K / (16 * KT);
+        splits = (int)(want < most ? want : most);
+        if (splits < 1) splits = 1;
+    } else if (allow_split && p.tiles <= 256 && K >= 16384) {
         const int64_t want = 4096 / p.tiles;          // aim at ~4096 workgroups
         const int64_t most = K / (16 * KT);           // at least 16 k-tiles per split
         splits = (int)(want < most ? want : most);
@@ -780,6 +858,7 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
     if (kps < KT) kps = KT;
     splits = (K + kps - 1) / kps;
     p.splits = splits; p.k_per_split = kps;
+    if (p.cover) { if (splits == 1) { p.cover = 0; p.tiles = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * G; } else return p; }
     const int64_t wgs = p.tiles * splits;
     if (wgs >= 512 || K < 256) p.kg = 1;             // enough blocks (or too little k to share)
     else if (wgs <= 192 && N > 32) { p.tile = 32; p.kg = 2; }   // kg: "many", resolved per dtype
@@ -898,7 +977,15 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
         GemmArgs pa = a;
         pa.C = a.partial; pa.ldc = a.N; pa.gC = (int64_t)a.M * a.N;
         const bool vecP = vec_c_ok(pa, EPI_PARTIAL, esz);
-        launch_small<D, AK, BKC, EPI_PARTIAL, VEC>(pa, p, vecP, st);
+        bool covered = false;
+        if constexpr (D::kBytes == 2) {
+            if (p.cover) {
+                launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI_PARTIAL, 256, 128, 2, 2, 1, 1, VEC, 64>, 256, pa, vecP,
+                                       p.splits, p.k_per_split, st);
+                covered = true;
+            }
+        }
+        if (!covered) launch_small<D, AK, BKC, EPI_PARTIAL, VEC>(pa, p, vecP, st);
         if (a.keep_partial) return hipGetLastError();
         const int64_t units = (int64_t)a.M * ((a.N + 7) / 8);
         dim3 g2((unsigned)((units + 255) / 256), 1, (unsigned)a.G);

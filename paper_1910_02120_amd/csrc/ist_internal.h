@@ -186,7 +186,7 @@ hipError_t launch_lse_combine(const float *pmax, const float *psum, int32_t nb, 
                               const float *zlabel, const int32_t *y, int64_t gY, int64_t Cn, float *lse,
                               float *rowloss, int32_t G, int32_t B, hipStream_t st);
 constexpr int kLseChunksHost = 32;   // second-level partials per row (matches the kernels)
-struct SplitPlan { int tile; int splits; int k_per_split; int kg; int64_t tiles; };
+struct SplitPlan { int tile; int splits; int k_per_split; int kg; int64_t tiles; int cover; /* 1: one 256x128 block per group and split */ };
 SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split, int esz);
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 // Number of k-splits launch_gemm uses for this product (1: none).  With a.keep_partial set, a split

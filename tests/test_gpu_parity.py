@@ -49,6 +49,9 @@ SHAPES = {
     # 64-wide lane groups of the narrow-output cross-entropy kernel; 300 classes take the wide kernel
     "many-steps-f32": _mk("many-steps-f32", "cfg2", dims=(48, 64, 130), S=2, B=10, k=19, lr=0.05),
     "mid-out-bf16": _mk("mid-out-bf16", "cfg3", dims=(64, 128, 300), S=4, B=12, k=2, lr=0.05),
+    # wide output layer with a full 256-row batch: the row-statistics pass takes its 256x256 blocks
+    "wide-out-bf16-B256": _mk("wide-out-bf16-B256", "cfg5", dims=(200, 512, 33001), S=8, B=256, k=2,
+                              nnz_per_row=10, lr=0.5),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
