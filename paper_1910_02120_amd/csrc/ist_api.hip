@@ -206,7 +206,9 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         size_t act_e = (l == t) ? sizeof(float) : (size_t)e;
         if (l == t && ctx->fused_out) act_e = 0;   // logits of a wide output layer are never stored
         L.off_act = w; w = align_up(w + (size_t)S * max_B * L.ldr * act_e);
-        L.off_dz = w;  w = align_up(w + (size_t)S * max_B * L.ldr * e);
+        // the dz of a wide output layer is kept transposed, [S][N_t][max_B rounded up to 8]
+        const size_t dz_elems = (l == t && ctx->fused_out) ? (size_t)S * L.R * ((max_B + 7) / 8 * 8) : (size_t)S * max_B * L.ldr;
+        L.off_dz = w;  w = align_up(w + dz_elems * e);
         if (ctx->normalize && l < t) {
             L.off_z = w;   w = align_up(w + (size_t)S * max_B * L.ldr * sizeof(float));
             L.off_zh = w;  w = align_up(w + (size_t)S * max_B * L.ldr * e);
@@ -658,6 +660,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
     const int t = ctx->t, S = ctx->S, e = ctx->esz(), B = bt->B, dt = ctx->dtype;
     char *ws = ctx->workspace, *sb = ctx->subnets;
     float *rowloss0 = reinterpret_cast<float *>(ws + ctx->off_rowloss);   // [kLossSlots][S][B]
+    const int64_t ldb = (B + 7) / 8 * 8;   // row pitch of the transposed dz of a wide output layer
 
 
     for (int j = 0; j < k; ++j) {
@@ -711,8 +714,17 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                                                            reinterpret_cast<float *>(ws + ctx->off_qsum), a.zlabel, a.y, a.gY, L.R,
                                                            reinterpret_cast<float *>(ws + ctx->off_lse), rowloss, S, B, st),
                         "combine row statistics");
-                a.C = ws + L.off_dz;
-                IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_DZ, a, st), "forward gemm (dz)");
+                // pass 2 with the operands exchanged: rows = classes, columns = samples, so that dz_t is
+                // written (and later read) as dz_t^T [N_t][ldb], whole tiles contiguous in memory
+                GemmArgs d{};
+                set_split(ctx, d);
+                d.A = a.B; d.sam = a.sbn; d.sak = 1; d.gA = a.gB;
+                d.B = a.A; d.sbn = a.sam; d.sbk = 1; d.gB = a.gA;
+                d.M = a.N; d.N = a.M; d.K = a.K; d.G = S;
+                d.C = ws + L.off_dz; d.ldc = ldb; d.gC = L.R * ldb;
+                d.bias = bias; d.gBias = L.R; d.alpha = a.alpha;
+                d.y = a.y; d.gY = a.gY; d.lse = a.lse; d.invB = a.invB;
+                IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_DZT, d, st), "forward gemm (dz, transposed)");
                 continue;
             }
             if (ctx->normalize && l < t) {
@@ -765,6 +777,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 GemmArgs a{};
                 set_split(ctx, a);
                 a.A = ws + L.off_dz; a.sam = L.ldr; a.sak = 1; a.gA = (int64_t)B * L.ldr;
+                if (l == t && ctx->fused_out) { a.sam = 1; a.sak = ldb; a.gA = L.R * ldb; }   // dz_t^T [N_t][ldb]
                 a.B = sb + L.off_W; a.sbn = 1; a.sbk = L.C; a.gB = L.R * L.C;
                 a.C = ws + P.off_dz; a.ldc = P.ldr; a.gC = (int64_t)B * P.ldr;
                 a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
@@ -785,6 +798,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 GemmArgs a{};
                 set_split(ctx, a);
                 a.A = ws + L.off_dz; a.sam = 1; a.sak = L.ldr; a.gA = (int64_t)B * L.ldr;
+                if (l == t && ctx->fused_out) { a.sam = ldb; a.sak = 1; a.gA = L.R * ldb; }   // dz_t^T [N_t][ldb]
                 if (l == 1) {
                     a.B = static_cast<const char *>(bt->x) + (size_t)row0 * L.C * e;
                     a.gB = bt->stride_s * L.C;
@@ -806,6 +820,11 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 ba.B = B; ba.G = S; ba.lr = lr;
                 for (int l = l0; l <= t && l < l0 + kMaxBiasJobs; ++l) {
                     const LayerPlan &L = ctx->layer[l - 1];
+                    if (l == t && ctx->fused_out) {
+                        IST_RUN(KC_BIAS_UPDATE, launch_bias_update_t(sb + L.off_b, ws + L.off_dz, L.R, ldb, B, S, lr, dt, st),
+                                "bias update (transposed dz)");
+                        continue;
+                    }
                     ba.job[ba.njobs++] = BiasJob{sb + L.off_b, ws + L.off_dz, L.R, L.ldr, 0};
                 }
                 IST_RUN(KC_BIAS_UPDATE, launch_bias_update(ba, dt, st), "bias update");

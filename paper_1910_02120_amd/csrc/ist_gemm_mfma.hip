@@ -298,69 +298,22 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
 }
 
 
-// EPI_LSE: the CPR lanes that hold the 8-column chunks of one row of the wave's column block
-// reduce max and sum(exp) of that block; logits are not stored.  All lanes take part.
-template <typename D, int CPR>
-__device__ inline void epi_lse(const GemmArgs &a, int g, int m, int n0, int blk, float (&val)[8],
-                               const float (&bias8)[8], int label)
-{
-    const bool rowok = m < a.M;
-    const int nv = !rowok ? 0 : (a.N - n0 >= 8 ? 8 : (a.N - n0 > 0 ? a.N - n0 : 0));
-#pragma unroll
-    for (int i = 0; i < 8; ++i) val[i] = fmaf(a.alpha, val[i], bias8[i]);
-    // exp(x) = exp2(x * log2(e)): scale once, then only v_exp_f32 per element
-    constexpr float kLog2e = 1.4426950408889634f;
-    float mx = -INFINITY, se = 0.0f;
-    if (nv == 8) {   // the common case, no per-element masks
-#pragma unroll
-        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, val[i]);
-#pragma unroll
-        for (int o = 1; o < CPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        const float ms = mx * kLog2e;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) se += __builtin_amdgcn_exp2f(fmaf(val[i], kLog2e, -ms));
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) mx = i < nv ? fmaxf(mx, val[i]) : mx;
-#pragma unroll
-        for (int o = 1; o < CPR; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-#pragma unroll
-        for (int i = 0; i < 8; ++i) se += i < nv ? __builtin_amdgcn_exp2f((val[i] - mx) * kLog2e) : 0.0f;
-    }
-#pragma unroll
-    for (int o = 1; o < CPR; o <<= 1) se += __shfl_xor(se, o);
-    if (!rowok) return;
-    if ((threadIdx.x & (CPR - 1)) == 0 && blk < a.nb) {
-        const int64_t pi = ((int64_t)g * a.nb + blk) * a.M + m;   // [g][block][row]: rows are the fast index
-        a.pmax[pi] = mx;
-        a.psum[pi] = se;
-    }
-    if (label >= n0 && label < n0 + nv) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (label == n0 + i) a.zlabel[(int64_t)g * a.M + m] = val[i];
-    }
-}
-
-// EPI_DZ: dz[m][n] = (exp(z - lse_m) - [n == y_m]) / B, stored in the storage dtype.
+// EPI_DZT: rows are classes, columns samples: dz^T[m][n] = (exp(z - lse_n) - [m == y_n]) / B in the storage
+// dtype.  ls8: the samples' log-sum-exp times log2(e), lab8 their labels, brow the bias of class m.
 template <typename D>
-__device__ inline void epi_dz(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC,
-                              const float (&bias8)[8], int label, float lse)
+__device__ inline void epi_dzt(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC, float brow,
+                               const int (&lab8)[8], const float (&ls8)[8])
 {
     using T = typename D::T;
     if (m >= a.M || n0 >= a.N) return;
     const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
     const bool vec = vecC && nv == 8;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) val[i] = fmaf(a.alpha, val[i], bias8[i]);
     constexpr float kLog2e = 1.4426950408889634f;
-    const float ls = lse * kLog2e;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) val[i] = __builtin_amdgcn_exp2f(fmaf(val[i], kLog2e, -ls)) * a.invB;
-    if (label >= n0 && label < n0 + 8) {   // rare: the chunk that holds the label
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (n0 + i == label) val[i] -= a.invB;
+    for (int i = 0; i < 8; ++i) {
+        const float z = fmaf(a.alpha, val[i], brow);
+        val[i] = __builtin_amdgcn_exp2f(fmaf(z, kLog2e, -ls8[i])) * a.invB;
+        val[i] = lab8[i] == m ? val[i] - a.invB : val[i];
     }
     Row8<T>::st(static_cast<T *>(a.C) + (int64_t)g * a.gC + (int64_t)m * a.ldc + n0, vec, nv, val);
 }
@@ -668,24 +621,33 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
         // per-row inputs of the cross-entropy epilogues, fetched in one batch up front
         // the 8 columns a lane finishes are the same in every row slice: one bias fetch per tile
         float bias8[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-        if ((EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS || EPI == EPI_LSE || EPI == EPI_DZ) && a.bias) {
+        if ((EPI == EPI_FWD_RELU || EPI == EPI_FWD_LOGITS) && a.bias) {
             const int n = cn0 + wn + 8 * (lane % CPR);
             const int nv = a.N - n >= 8 ? 8 : (a.N - n > 0 ? a.N - n : 0);
             if (nv > 0)
                 Row8<typename D::T>::ld(static_cast<const typename D::T *>(a.bias) + (int64_t)cg * a.gBias + n,
                                         vecC && nv == 8, nv, bias8);
         }
-        int lab[TM][32 / RPP];
-        float lsv[TM][32 / RPP];
-        if (EPI == EPI_LSE || EPI == EPI_DZ) {
+        // EPI_DZT: per tile, the labels and log-sum-exp of the 8 samples (columns) a lane finishes, and the
+        // bias of each class (row) it will meet
+        int lab8[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
+        float ls8[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+        float brow[TM][32 / RPP];
+        if (EPI == EPI_DZT) {
+            const int n = cn0 + wn + 8 * (lane % CPR);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = n + e < a.N;
+                lab8[e] = ok ? a.y[(int64_t)cg * a.gY + n + e] : -1;
+                ls8[e] = ok ? a.lse[(int64_t)cg * a.N + n + e] * 1.4426950408889634f : 0.0f;
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int p = 0; p < 32 / RPP; ++p) {
                     const int m = cm0 + wm + i * 32 + p * RPP + lane / CPR;
-                    const bool ok = m < a.M;
-                    lab[i][p] = ok ? a.y[(int64_t)cg * a.gY + m] : -1;
-                    lsv[i][p] = (EPI == EPI_DZ && ok) ? a.lse[(int64_t)cg * a.M + m] : 0.0f;
+                    brow[i][p] = (a.bias && m < a.M)
+                                     ? D::ld(static_cast<const typename D::T *>(a.bias) + (int64_t)cg * a.gBias + m) : 0.0f;
                 }
         }
         // Old weights (update) / activations (ReLU mask) of the chunks this lane will finish,
@@ -739,11 +701,8 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
                     const float4 x = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch);
                     const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
                     float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-                    if (EPI == EPI_LSE)
-                        epi_lse<D, CPR>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, (cn0 + wn) / (32 * TN), val, bias8,
-                                        lab[i][p]);
-                    else if (EPI == EPI_DZ)
-                        epi_dz<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, bias8, lab[i][p], lsv[i][p]);
+                    if (EPI == EPI_DZT)
+                        epi_dzt<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, brow[i][p], lab8, ls8);
                     else
                         epi8<D, EPI, PRE>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
                                           val, vecC, bias8, pre[i % PD][p]);
@@ -801,9 +760,8 @@ static bool vec_c_ok(const GemmArgs &a, int epi, int esz)
     const int ch = 16 / out_esz;
     bool ok = reinterpret_cast<uintptr_t>(a.C) % 16 == 0 && a.gC % ch == 0 && a.ldc % ch == 0;
     const int che = 16 / esz;
-    if (epi == EPI_LSE)   // nothing is stored: the flag only covers the bias reads
-        return !a.bias || (reinterpret_cast<uintptr_t>(a.bias) % 16 == 0 && a.gBias % (16 / esz) == 0);
-    if ((epi == EPI_FWD_RELU || epi == EPI_FWD_LOGITS || epi == EPI_DZ) && a.bias)
+    if (epi == EPI_LSE) return true;   // nothing is stored, the bias is read per element
+    if ((epi == EPI_FWD_RELU || epi == EPI_FWD_LOGITS) && a.bias)
         ok = ok && reinterpret_cast<uintptr_t>(a.bias) % 16 == 0 && a.gBias % che == 0;
     if (epi == EPI_BWD_DATA)
         ok = ok && reinterpret_cast<uintptr_t>(a.mask) % 16 == 0 && a.gMask % che == 0 && a.ldm % che == 0;
@@ -914,7 +872,7 @@ static void launch_small(const GemmArgs &a, const SplitPlan &p, bool vecC, hipSt
 // the plan of one launch: k is split only where the epilogue allows it and the scratch buffer is large enough
 static SplitPlan plan_for(const GemmArgs &a, int epi, int esz)
 {
-    const bool can_split = epi != EPI_UPDATE && epi != EPI_LSE && epi != EPI_DZ && a.partial != nullptr;
+    const bool can_split = epi != EPI_UPDATE && epi != EPI_LSE && epi != EPI_DZT && a.partial != nullptr;
     SplitPlan p = plan_gemm(a.M, a.N, a.K, a.G, can_split, esz);
     if (p.splits > 1 && (size_t)a.G * p.splits * a.M * a.N * sizeof(float) > a.partial_bytes)
         p = plan_gemm(a.M, a.N, a.K, a.G, false, esz);
@@ -932,7 +890,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
 {
     const int esz = D::kBytes;
     const bool vecC = vec_c_ok(a, EPI, esz);
-    static const char *const kEpi[] = {"fwd_relu", "fwd_logits", "bwd_data", "update", "partial", "fwd_lse", "fwd_dz"};
+    static const char *const kEpi[] = {"fwd_relu", "fwd_logits", "bwd_data", "update", "partial", "fwd_lse", "fwd_dzt"};
     static thread_local char lab[40];
     snprintf(lab, sizeof(lab), "%s_%s%s", kEpi[EPI], esz == 2 ? "bf16" : "f32", VEC ? "" : "_novec");
     s_label = lab;
@@ -1019,14 +977,16 @@ static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
     case EPI_LSE:
         if (a_k && b_k) return launch_cfg<D, true, true, EPI_LSE>(a, st);
         break;
-    case EPI_DZ:
-        if (a_k && b_k) return launch_cfg<D, true, true, EPI_DZ>(a, st);
+    case EPI_DZT:
+        if (a_k && b_k) return launch_cfg<D, true, true, EPI_DZT>(a, st);
         break;
     case EPI_BWD_DATA:
         if (a_k && b_n) return launch_cfg<D, true, false, EPI_BWD_DATA>(a, st);
+        if (a_m && b_n) return launch_cfg<D, false, false, EPI_BWD_DATA>(a, st);   // dz stored transposed
         break;
     case EPI_UPDATE:
         if (a_m && b_n) return launch_cfg<D, false, false, EPI_UPDATE>(a, st);
+        if (a_k && b_n) return launch_cfg<D, true, false, EPI_UPDATE>(a, st);      // dz stored transposed
         break;
     default: break;
     }

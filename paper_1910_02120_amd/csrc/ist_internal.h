@@ -157,7 +157,9 @@ hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc,
 enum Epilogue {
     EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3, EPI_PARTIAL = 4,
     EPI_LSE = 5,   // logits are not stored: per row and column block, max and sum of exp (wide output layers)
-    EPI_DZ = 6     // logits recomputed: store dz = (exp(z - lse) - onehot) / B in the storage dtype
+    EPI_DZT = 6    // logits recomputed with the roles of the operands exchanged (rows = classes, columns = samples):
+                   // store dz^T[n][b] = (exp(z[b][n] - lse[b]) - [n == y_b]) / B in the storage dtype.  A tile of
+                   // dz^T is one contiguous piece of memory; a tile of dz [b][n] would be 128 pieces 2 N_t bytes apart
 };
 
 // C[g][m][n] (+)= sum_k A_g(m,k) * B_g(n,k), element (m,k) of A at A + g*gA + m*sam + k*sak.
@@ -173,11 +175,11 @@ struct GemmArgs {
     float *partial; size_t partial_bytes;     // split-K scratch (fp32 partial products), may be null
     int32_t keep_partial;                     // host flag: a k-split launch leaves the partial products unfinished
     const void *zeros;                        // >= 16 bytes of zeros, 16-byte aligned (MFMA kernels)
-    // EPI_LSE / EPI_DZ (softmax cross-entropy over a wide output layer, logits never stored)
+    // EPI_LSE / EPI_DZT (softmax cross-entropy over a wide output layer, logits never stored)
     const int32_t *y; int64_t gY;             // labels of the batch rows, per-group stride
     float *pmax, *psum; int32_t nb;           // [G][M][nb] per column block: max, sum exp(z - max)
     float *zlabel;                            // [G][M] logit of the label
-    const float *lse;                         // [G][M] log-sum-exp of the row (EPI_DZ)
+    const float *lse;                         // EPI_DZT: [G][N] log-sum-exp of the sample (a column there; y likewise)
     float invB;
 };
 // column-block width (elements) the EPI_LSE epilogue reduces over, for this problem shape
@@ -220,6 +222,9 @@ hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int3
 // loss_out[g * out_stride_g + j] = mean_b rowloss[j][g][b], j < nsteps
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
                               int32_t G, int32_t B, int32_t nsteps, hipStream_t st);
+// bias[g][r] -= lr * sum_{b < B} dzt[g][r][b] for a dz stored transposed ([G][R][ldb], ldb a multiple of 8)
+hipError_t launch_bias_update_t(void *bias, const void *dzt, int64_t R, int64_t ldb, int32_t B, int32_t G, float lr,
+                                int dtype, hipStream_t st);
 struct BiasJob { void *bias; const void *dz; int64_t R, ld; int32_t blk0; };
 constexpr int kMaxBiasJobs = 16;
 struct BiasArgs { BiasJob job[kMaxBiasJobs]; int32_t njobs, B, G; float lr; };

@@ -232,7 +232,7 @@ def test_profile_records_name_kernels_and_work():
     ctx.close()
 
 
-@pytest.mark.parametrize("name", ["ragged-f32", "ragged-bf16", "csr-f32"])
+@pytest.mark.parametrize("name", ["ragged-f32", "ragged-bf16", "csr-f32", "cfg5-small", "wide-out-f32"])
 def test_batch_smaller_than_max_B(name):
     """A context sized for max_B runs smaller batches: same result as a context sized exactly."""
     from paper_1910_02120_amd import ISTContext
@@ -245,6 +245,27 @@ def test_batch_smaller_than_max_B(name):
     P.oracle_steps(subs)
     H.compare_subnets(H.export_all(big, cfg), subs, cfg, H.TOL[cfg.dtype])
     big.close()
+
+
+@pytest.mark.parametrize("name", ["cfg5-small", "wide-out-f32", "ragged-bf16"])
+def test_smaller_batch_after_a_larger_one(name):
+    """The same context first trains on its largest batch, then, from a fresh partition, on a batch three
+    samples shorter: what the first run left in the workspace (among it the columns of the transposed dz
+    of a wide output layer beyond the new batch size) must not leak into the second."""
+    cfg = SHAPES[name]
+    small = gen.scaled(cfg, B=cfg.B - 3)
+    Pb, Ps = H.Problem(cfg, dev=_dev()), H.Problem(small, dev=_dev())
+    ctx = Pb.context()
+    ctx.partition(Pb.dW, Pb.db, Pb.dperm)
+    Pb.gpu_steps(ctx)
+    ctx.partition(Ps.dW, Ps.db, Ps.dperm)
+    loss = Ps.gpu_steps(ctx)
+    subs = Ps.oracle_subnets()
+    want_loss = Ps.oracle_steps(subs)
+    tol = H.TOL[cfg.dtype]
+    H.compare_subnets(H.export_all(ctx, small), subs, small, tol)
+    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
+    ctx.close()
 
 
 def test_csr_with_empty_rows_and_unused_columns():
