@@ -661,6 +661,8 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
     char *ws = ctx->workspace, *sb = ctx->subnets;
     float *rowloss0 = reinterpret_cast<float *>(ws + ctx->off_rowloss);   // [kLossSlots][S][B]
     const int64_t ldb = (B + 7) / 8 * 8;   // row pitch of the transposed dz of a wide output layer
+    std::vector<GemmArgs> upd;
+    upd.reserve((size_t)t);
 
 
     for (int j = 0; j < k; ++j) {
@@ -810,9 +812,16 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.C = sb + L.off_W; a.ldc = L.C; a.gC = L.R * L.C;
                 a.M = (int32_t)L.R; a.N = (int32_t)L.C; a.K = B; a.G = S;
                 a.lr = lr * ctx->scale[l - 1];   // dW_l = gamma_l dz_l^T h_{l-1}
-                IST_RUN(KC_GEMM_UPDATE, launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
+                upd.push_back(a);
             }
         }
+        // The updates only need the dz_l (all final by now) and nothing reads W_l any more in this step:
+        // they go out together, small layers in one launch.
+        for (size_t u0 = 0; u0 < upd.size(); u0 += 4) {
+            const int nu = (int)std::min<size_t>(4, upd.size() - u0);
+            IST_RUN(KC_GEMM_UPDATE, launch_gemm_updates(dt, upd.data() + u0, nu, st), "backward-weight gemm");
+        }
+        upd.clear();
         // all bias updates of the step in one launch (they only need the dz_l of this step)
         if (ctx->has_bias) {
             for (int l0 = 1; l0 <= t; l0 += kMaxBiasJobs) {

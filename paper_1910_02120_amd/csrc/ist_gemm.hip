@@ -130,6 +130,16 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
     return force_generic() ? launch_gemm_generic(dtype, epi, a, st) : launch_gemm_mfma(dtype, epi, a, st);
 }
 
+hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, hipStream_t st)
+{
+    if (!force_generic()) return launch_gemm_updates_mfma(dtype, args, n, st);
+    for (int i = 0; i < n; ++i) {
+        hipError_t e = launch_gemm_generic(dtype, EPI_UPDATE, args[i], st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 int gemm_splits(int dtype, int epi, const GemmArgs &a)
 {
     return force_generic() ? 1 : gemm_splits_mfma(dtype, epi, a);

@@ -325,14 +325,12 @@ template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; }
 // WM x WN wavefronts tile the BM x BN block, KG k-groups share it: 64*WM*WN*KG threads.
 // DB: two LDS tile buffers and one barrier per k-tile (ST = 1, KG = 1, not PERSIST): the LDS
 // stores of tile i+1 and the global loads of tile i+2 are issued ahead of the MFMAs of tile i.
+// bid / nblk: this workgroup's index among the nblk workgroups that share the product (the grid of a
+// plain launch; a slice of it when one launch carries several products).
 template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
-          bool PERSIST = (EPI == EPI_UPDATE), bool DB = false>
-__global__ __launch_bounds__(64 * WM * WN * KG,
-                             // waves per SIMD the register allocator must leave room for: 2 for the
-                             // 128x64 wave tile (128 accumulator registers), 3 for the 64x64 one (bf16 kernels)
-                             (D::kBytes != 2) ? 1 : ((BM / (32 * WM)) * (BN / (32 * WN)) >= 8) ? 2 : ((KG == 1 && BM >= 128) ? 3 : 1))
-void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x, int tiles_y, int stagger,
-                 int stagger_sleeps)
+          bool PERSIST, bool DB>
+__device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int splits, int k_per_split, int tiles_x,
+                                          int tiles_y, int stagger, int stagger_sleeps, int bid, int nblk)
 {
     using M = Mma<D, KT>;
     using E = typename M::E;
@@ -360,11 +358,11 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
     float *fsm = reinterpret_cast<float *>(smem);
 
     // Block tiles are numbered n-fastest, then m, then (group, split); a workgroup takes
-    // tiles t = blockIdx.x, blockIdx.x + gridDim.x, ... and issues the first loads of its
+    // tiles t = bid, bid + nblk, ... and issues the first loads of its
     // next tile before the epilogue of the current one.
     const int per_z = tiles_x * tiles_y;
     const int total = per_z * a.G * splits;
-    int t = blockIdx.x;
+    int t = bid;
     int g, gz, m0, n0, kbeg, kend;
     const E *A, *B;
     auto decode = [&](int tt) {
@@ -385,7 +383,7 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
     // MFMA-bound main loop and the HBM-bound epilogue in lockstep, leaving each resource idle
     // half of the time.  Start them in `stagger` phase groups a fraction of a tile apart.
     if (PERSIST && DB && stagger > 1) {
-        const int phase = (blockIdx.x >> 3) % stagger;   // blockIdx.x & 7 selects the XCD
+        const int phase = (bid >> 3) % stagger;   // bid & 7 selects the XCD
         for (int i = 0; i < phase * stagger_sleeps; ++i) __builtin_amdgcn_s_sleep(127);
     }
 
@@ -540,7 +538,7 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
         // ---- first loads of the next tile, so that they fly during this epilogue ----
         // (only where workgroups walk several tiles: the extra live state costs registers)
         const int cg = g, cgz = gz, cm0 = m0, cn0 = n0;
-        const int tn = t + (int)gridDim.x;
+        const int tn = t + nblk;
         const bool more = PERSIST && tn < total;
         if (PERSIST) {
             decode(more ? tn : t);   // unconditional (a last tile re-reads its own first k-tile):
@@ -715,6 +713,48 @@ void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x
         t = tn;
         __syncthreads();   // staging reads are done before the next tile's LDS stores
     }
+}
+
+// waves per SIMD the register allocator must leave room for: 2 for the 128x64 wave tile (128 accumulator
+// registers), 3 for the 64x64 one (bf16 kernels)
+#define IST_GEMM_BOUNDS                                                                                            \
+    __launch_bounds__(64 * WM * WN * KG,                                                                           \
+                      (D::kBytes != 2) ? 1 : ((BM / (32 * WM)) * (BN / (32 * WN)) >= 8) ? 2 : ((KG == 1 && BM >= 128) ? 3 : 1))
+
+template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
+          bool PERSIST = (EPI == EPI_UPDATE), bool DB = false>
+__global__ IST_GEMM_BOUNDS
+void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x, int tiles_y, int stagger,
+                 int stagger_sleeps)
+{
+    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB>(a, vecC, splits, k_per_split, tiles_x, tiles_y,
+                                                                              stagger, stagger_sleeps, (int)blockIdx.x,
+                                                                              (int)gridDim.x);
+}
+
+// Several independent products of one shape class in one launch (the weight updates of all layers of a
+// small network: each alone leaves most of the chip idle while it fills and drains).  Workgroups
+// first[i] .. first[i+1]-1 work on product i.
+constexpr int kMaxMulti = 4;
+struct GemmMulti {
+    GemmArgs p[kMaxMulti];
+    int first[kMaxMulti + 1];
+    int tiles_x[kMaxMulti], tiles_y[kMaxMulti], vecC[kMaxMulti];
+    int n;
+};
+
+template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
+          bool PERSIST = (EPI == EPI_UPDATE), bool DB = false>
+__global__ IST_GEMM_BOUNDS
+void k_gemm_mfma_multi(GemmMulti mm)
+{
+    int i = 0;
+    while (i + 1 < mm.n && (int)blockIdx.x >= mm.first[i + 1]) ++i;
+    const GemmArgs a = mm.p[i];
+    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB>(a, mm.vecC[i] != 0, 1, a.K, mm.tiles_x[i],
+                                                                              mm.tiles_y[i], 0, 0,
+                                                                              (int)blockIdx.x - mm.first[i],
+                                                                              mm.first[i + 1] - mm.first[i]);
 }
 
 // out[g][m][n] = epilogue(sum_sp partial[g*splits + sp][m][n]) for split-K launches.
@@ -997,6 +1037,53 @@ int lse_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G)
 {
     const SplitPlan p = plan_gemm(M, N, K, G, false, dtype == IST_BF16 ? 2 : 4);
     return p.tile == 128 ? 64 : 32;   // 32 * TN of the configuration launch_vec picks
+}
+
+// The update products of several layers.  Those that take the small persistent 64x64 kernel with 16-byte
+// operand loads (every layer of the small f32 configurations) share one launch; any other goes out alone
+// (sharing a launch among 128x128-block products was measured and gains nothing: they already fill the chip).
+template <typename D>
+static hipError_t launch_updates_typed(const GemmArgs *args, int n, hipStream_t st)
+{
+    const int esz = D::kBytes;
+    GemmMulti mm{};
+    double flops = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const GemmArgs &a = args[i];
+        if (a.M <= 0 || a.N <= 0 || a.G <= 0) continue;
+        const bool layout = a.sam == 1 && a.sbn == 1 && a.sak != 1 && a.sbk != 1;
+        const bool vec = vec_ok(a.A, a.gA, a.sak, esz) && vec_ok(a.B, a.gB, a.sbk, esz);
+        const SplitPlan p = plan_for(a, EPI_UPDATE, esz);
+        const int tx = (a.N + 63) / 64, ty = (a.M + 63) / 64;
+        const int64_t total = (int64_t)tx * ty * a.G;
+        if (!layout || !vec || p.tile == 128 || mm.n == kMaxMulti || total > (1 << 20)) {
+            hipError_t e = launch_dtype<D>(EPI_UPDATE, a, st);
+            if (e != hipSuccess) return e;
+            continue;
+        }
+        const int64_t cap = 256 * 3 * 4;
+        mm.p[mm.n] = a;
+        mm.tiles_x[mm.n] = tx; mm.tiles_y[mm.n] = ty;
+        mm.vecC[mm.n] = vec_c_ok(a, EPI_UPDATE, esz) ? 1 : 0;
+        mm.first[mm.n + 1] = mm.first[mm.n] + (int)(total >= 4 * cap ? cap : total);
+        flops += 2.0 * a.M * a.N * (double)a.K * a.G;
+        ++mm.n;
+    }
+    if (mm.n == 0) return hipGetLastError();
+    if (mm.n == 1) return launch_dtype<D>(EPI_UPDATE, mm.p[0], st);
+    char label[64];
+    snprintf(label, sizeof(label), "gemm_update_%s_64x64_t256_persistent_x%d", esz == 2 ? "bf16" : "f32", mm.n);
+    tag_kernel(label, flops, 0.0);
+    hipLaunchKernelGGL((k_gemm_mfma_multi<D, false, false, EPI_UPDATE, 64, 64, 2, 2, 1, 3, true, 32>), dim3((unsigned)mm.first[mm.n]),
+                       dim3(256), 0, st, mm);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, hipStream_t st)
+{
+    for (int i = 0; i < n; ++i)
+        if (args[i].zeros == nullptr) return hipErrorInvalidValue;
+    return dtype == IST_BF16 ? launch_updates_typed<BF16>(args, n, st) : launch_updates_typed<F32>(args, n, st);
 }
 
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st)

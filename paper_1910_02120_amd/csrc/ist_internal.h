@@ -198,6 +198,9 @@ int gemm_splits(int dtype, int epi, const GemmArgs &a);
 hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a);
+// The EPI_UPDATE products of several layers (independent of each other); small ones share one launch.
+hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, hipStream_t st);
+hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, hipStream_t st);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
