@@ -35,8 +35,9 @@ EVENT_OVERHEAD_US = 2.4
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the 1 GiB copy of
 # --calibrate-copy; the runs and the scale factors are in profiles/.  {workload: {kernel label: bytes}}
 MEASURED_TRAFFIC = {
-    # read 25.06 MB (FETCH_SIZE 12235.7 KiB x 2.000) + written 11.38 MB (WRITE_SIZE 11109.3 KiB x 1.000)
-    "cfg2": {"gemm_update_f32_64x64_t256_persistent": 36.44e6},
+    # the three update products of a step in one launch:
+    # read 74.85 MB (FETCH_SIZE 36547.1 KiB x 2.000) + written 34.13 MB (WRITE_SIZE 33328.0 KiB x 1.000)
+    "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3": 108.98e6},
     # read 1690.6 MB (825494.7 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000)
     "cfg4": {"gemm_update_bf16_256x256_t512_persistent": 2585.3e6},
 }

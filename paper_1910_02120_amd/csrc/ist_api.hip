@@ -224,6 +224,9 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         ctx->off_qsum = w; w = align_up(w + sizeof(float) * rows * kLseChunksHost);
         ctx->off_zlabel = w; w = align_up(w + sizeof(float) * rows);
         ctx->off_lse = w; w = align_up(w + sizeof(float) * rows);
+        // bias gradient of the output layer as partial sums per class and block of >= 32 samples
+        if (ctx->has_bias)
+            { ctx->off_rsum = w; w = align_up(w + sizeof(float) * (size_t)S * ((max_B + 31) / 32) * ctx->dims[t]); }
     }
     ctx->off_zeros = w; w = align_up(w + 256);   // stays zero: source of out-of-range operand chunks
     ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)kLossSlots * S * max_B);
@@ -668,7 +671,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
     for (int j = 0; j < k; ++j) {
         const int64_t row0 = (int64_t)j * bt->stride_k;
         float *rowloss = rowloss0 + (size_t)(j % kLossSlots) * S * B;
-        int out_splits = 1;
+        int out_splits = 1, out_nrb = 0;
         // ---------------- forward ----------------
         for (int l = 1; l <= t; ++l) {
             const LayerPlan &L = ctx->layer[l - 1];
@@ -726,6 +729,11 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 d.C = ws + L.off_dz; d.ldc = ldb; d.gC = L.R * ldb;
                 d.bias = bias; d.gBias = L.R; d.alpha = a.alpha;
                 d.y = a.y; d.gY = a.gY; d.lse = a.lse; d.invB = a.invB;
+                if (ctx->has_bias) {
+                    const int rw = dzt_block_width(dt, d.M, d.N, d.K, d.G);
+                    d.pmax = reinterpret_cast<float *>(ws + ctx->off_rsum);   // here: partial bias gradients
+                    d.nb = out_nrb = (B + rw - 1) / rw;
+                }
                 IST_RUN(KC_GEMM_FWD, launch_gemm(dt, EPI_DZT, d, st), "forward gemm (dz, transposed)");
                 continue;
             }
@@ -830,8 +838,9 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 for (int l = l0; l <= t && l < l0 + kMaxBiasJobs; ++l) {
                     const LayerPlan &L = ctx->layer[l - 1];
                     if (l == t && ctx->fused_out) {
-                        IST_RUN(KC_BIAS_UPDATE, launch_bias_update_t(sb + L.off_b, ws + L.off_dz, L.R, ldb, B, S, lr, dt, st),
-                                "bias update (transposed dz)");
+                        IST_RUN(KC_BIAS_UPDATE, launch_bias_apply(sb + L.off_b, reinterpret_cast<const float *>(ws + ctx->off_rsum),
+                                                                  out_nrb, L.R, S, lr, dt, st),
+                                "bias update (from the partial sums of the dz pass)");
                         continue;
                     }
                     ba.job[ba.njobs++] = BiasJob{sb + L.off_b, ws + L.off_dz, L.R, L.ldr, 0};

@@ -300,12 +300,13 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
 
 // EPI_DZT: rows are classes, columns samples: dz^T[m][n] = (exp(z - lse_n) - [m == y_n]) / B in the storage
 // dtype.  ls8: the samples' log-sum-exp times log2(e), lab8 their labels, brow the bias of class m.
+// Returns the sum of the values as stored (the chunk's share of the bias gradient of class m).
 template <typename D>
-__device__ inline void epi_dzt(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC, float brow,
-                               const int (&lab8)[8], const float (&ls8)[8])
+__device__ inline float epi_dzt(const GemmArgs &a, int g, int m, int n0, float (&val)[8], bool vecC, float brow,
+                                const int (&lab8)[8], const float (&ls8)[8])
 {
     using T = typename D::T;
-    if (m >= a.M || n0 >= a.N) return;
+    if (m >= a.M || n0 >= a.N) return 0.0f;
     const int nv = a.N - n0 < 8 ? a.N - n0 : 8;
     const bool vec = vecC && nv == 8;
     constexpr float kLog2e = 1.4426950408889634f;
@@ -316,6 +317,10 @@ __device__ inline void epi_dzt(const GemmArgs &a, int g, int m, int n0, float (&
         val[i] = lab8[i] == m ? val[i] - a.invB : val[i];
     }
     Row8<T>::st(static_cast<T *>(a.C) + (int64_t)g * a.gC + (int64_t)m * a.ldc + n0, vec, nv, val);
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += i < nv ? D::up(D::cvt(val[i])) : 0.0f;
+    return s;
 }
 
 template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; };
@@ -328,10 +333,13 @@ template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; }
 // bid / nblk: this workgroup's index among the nblk workgroups that share the product (the grid of a
 // plain launch; a slice of it when one launch carries several products).
 template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
-          bool PERSIST, bool DB>
+          bool PERSIST, bool DB, bool SLICE>
 __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int splits, int k_per_split, int tiles_x,
-                                          int tiles_y, int stagger, int stagger_sleeps, int bid, int nblk)
+                                          int tiles_y, int stagger, int stagger_sleeps, int bid_, int nblk_)
 {
+    // a plain launch reads its position from the hardware registers (passing them through arguments was seen to
+    // cost registers: a kernel at its limit started to spill)
+    const int bid = SLICE ? bid_ : (int)blockIdx.x, nblk = SLICE ? nblk_ : (int)gridDim.x;
     using M = Mma<D, KT>;
     using E = typename M::E;
     constexpr int WQ = WM * WN;
@@ -601,12 +609,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
                     const int rel = label - ncol0;
                     const bool hit = rel >= 0 && rel < 32 * TN && ((rel >> 2) & 1) == half;
                     if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+                        // which of the lane's registers: block j = rel / 32, v = 4 (r / 8) + r % 4 with r = rel % 32
+                        const int want = hit ? (rel >> 5) * 16 + 4 * ((rel & 31) >> 3) + (rel & 3) : -1;
                         float zl = 0.0f;
 #pragma unroll
                         for (int j = 0; j < TN; ++j)
 #pragma unroll
-                            for (int v = 0; v < 16; ++v)
-                                zl = (32 * j + 8 * (v / 4) + 4 * half + v % 4 == rel) ? acc[i][j][v] : zl;
+                            for (int v = 0; v < 16; ++v) zl = (16 * j + v == want) ? acc[i][j][v] : zl;
                         if (hit) a.zlabel[(int64_t)cg * a.M + m] = zl;
                     }
                 }
@@ -699,9 +708,20 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
                     const float4 x = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch);
                     const float4 y = *reinterpret_cast<const float4 *>(stage + row * LDC + 8 * ch + 4);
                     float val[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-                    if (EPI == EPI_DZT)
-                        epi_dzt<D>(a, cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch, val, vecC, brow[i][p], lab8, ls8);
-                    else
+                    if (EPI == EPI_DZT) {
+                        const int m = cm0 + wm + i * 32 + row;
+                        float s = epi_dzt<D>(a, cg, m, cn0 + wn + 8 * ch, val, vecC, brow[i][p], lab8, ls8);
+                        if (a.pmax) {   // the CPR lanes of a row add their chunks up (all lanes of the wave are here)
+                            static_assert(CPR == 4 || CPR == 8, "row groups of 4 or 8 lanes");
+                            // lane ^ 1, lane ^ 2 (quad permutations), then 7 - lane within the group of 8
+                            s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0xB1, 0xF, 0xF, true));
+                            s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x4E, 0xF, 0xF, true));
+                            if (CPR == 8)
+                                s += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), 0x141, 0xF, 0xF, true));
+                            const int blk = (cn0 + wn) / (32 * TN);
+                            if (ch == 0 && m < a.M && blk < a.nb) a.pmax[((int64_t)cg * a.nb + blk) * a.M + m] = s;
+                        }
+                    } else
                         epi8<D, EPI, PRE>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
                                           val, vecC, bias8, pre[i % PD][p]);
                 }
@@ -719,7 +739,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
 // registers), 3 for the 64x64 one (bf16 kernels)
 #define IST_GEMM_BOUNDS                                                                                            \
     __launch_bounds__(64 * WM * WN * KG,                                                                           \
-                      (D::kBytes != 2) ? 1 : ((BM / (32 * WM)) * (BN / (32 * WN)) >= 8) ? 2 : ((KG == 1 && BM >= 128) ? 3 : 1))
+                      (D::kBytes != 2) ? 1 : ((BM / (32 * WM)) * (BN / (32 * WN)) >= 8) ? 2                          \
+                                               : ((KG == 1 && BM >= 128) ? 3 : 1))
 
 template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
           bool PERSIST = (EPI == EPI_UPDATE), bool DB = false>
@@ -727,9 +748,8 @@ __global__ IST_GEMM_BOUNDS
 void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x, int tiles_y, int stagger,
                  int stagger_sleeps)
 {
-    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB>(a, vecC, splits, k_per_split, tiles_x, tiles_y,
-                                                                              stagger, stagger_sleeps, (int)blockIdx.x,
-                                                                              (int)gridDim.x);
+    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB, false>(a, vecC, splits, k_per_split, tiles_x,
+                                                                                     tiles_y, stagger, stagger_sleeps, 0, 0);
 }
 
 // Several independent products of one shape class in one launch (the weight updates of all layers of a
@@ -751,10 +771,10 @@ void k_gemm_mfma_multi(GemmMulti mm)
     int i = 0;
     while (i + 1 < mm.n && (int)blockIdx.x >= mm.first[i + 1]) ++i;
     const GemmArgs a = mm.p[i];
-    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB>(a, mm.vecC[i] != 0, 1, a.K, mm.tiles_x[i],
-                                                                              mm.tiles_y[i], 0, 0,
-                                                                              (int)blockIdx.x - mm.first[i],
-                                                                              mm.first[i + 1] - mm.first[i]);
+    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB, true>(a, mm.vecC[i] != 0, 1, a.K, mm.tiles_x[i],
+                                                                                    mm.tiles_y[i], 0, 0,
+                                                                                    (int)blockIdx.x - mm.first[i],
+                                                                                    mm.first[i + 1] - mm.first[i]);
 }
 
 // out[g][m][n] = epilogue(sum_sp partial[g*splits + sp][m][n]) for split-K launches.
@@ -1031,6 +1051,13 @@ static hipError_t launch_dtype(int epi, const GemmArgs &a, hipStream_t st)
     default: break;
     }
     return hipErrorInvalidValue;
+}
+
+int dzt_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G)
+{
+    const SplitPlan p = plan_gemm(M, N, K, G, false, dtype == IST_BF16 ? 2 : 4);
+    // 64x64 and 64x32 blocks: wave tiles 32 columns wide; 128x128, 256x128 and 256x256 blocks: 64 columns
+    return p.tile == 128 ? 64 : 32;
 }
 
 int lse_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G)

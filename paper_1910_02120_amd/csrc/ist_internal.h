@@ -84,7 +84,7 @@ struct ist_ctx {
     size_t off_rowloss = 0, off_bitmap = 0, off_err = 0;  // workspace
     size_t off_partial = 0, partial_bytes = 0, off_zeros = 0;
     bool fused_out = false;   // wide output layer: logits are never stored
-    size_t off_pmax = 0, off_psum = 0, off_qmax = 0, off_qsum = 0, off_zlabel = 0, off_lse = 0; int32_t nb_max = 0;
+    size_t off_pmax = 0, off_psum = 0, off_qmax = 0, off_qsum = 0, off_zlabel = 0, off_lse = 0, off_rsum = 0; int32_t nb_max = 0;
     char *subnets = nullptr;
     char *spare = nullptr;      // second subnet buffer: target of ist_resample, then swapped in
     char *workspace = nullptr;
@@ -181,9 +181,15 @@ struct GemmArgs {
     float *zlabel;                            // [G][M] logit of the label
     const float *lse;                         // EPI_DZT: [G][N] log-sum-exp of the sample (a column there; y likewise)
     float invB;
+    // EPI_DZT reuses pmax / nb (optional, pmax may be null): pmax[(g * nb + blk) * M + m] = sum over the samples of
+    // column block blk (as wide as a wave tile) of the stored dz^T[m][.] - the bias gradient in nb partials per class,
+    // added up in order by the bias kernel.  (A separate pair of fields would lengthen the argument block of every
+    // instantiation; the row-statistics kernel was measured 13 % slower with it.)
 };
 // column-block width (elements) the EPI_LSE epilogue reduces over, for this problem shape
 int lse_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G);
+// the same for the sample (column) blocks of the EPI_DZT launch of this shape (M = classes, N = samples)
+int dzt_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G);
 hipError_t launch_lse_combine(const float *pmax, const float *psum, int32_t nb, float *qmax, float *qsum,
                               const float *zlabel, const int32_t *y, int64_t gY, int64_t Cn, float *lse,
                               float *rowloss, int32_t G, int32_t B, hipStream_t st);
@@ -225,9 +231,9 @@ hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int3
 // loss_out[g * out_stride_g + j] = mean_b rowloss[j][g][b], j < nsteps
 hipError_t launch_loss_reduce(const float *rowloss, float *loss_out, int64_t out_stride_g,
                               int32_t G, int32_t B, int32_t nsteps, hipStream_t st);
-// bias[g][r] -= lr * sum_{b < B} dzt[g][r][b] for a dz stored transposed ([G][R][ldb], ldb a multiple of 8)
-hipError_t launch_bias_update_t(void *bias, const void *dzt, int64_t R, int64_t ldb, int32_t B, int32_t G, float lr,
-                                int dtype, hipStream_t st);
+// bias[g][r] -= lr * sum_{blk < nrb} rsum[(g * nrb + blk) * R + r], blocks added in ascending order
+hipError_t launch_bias_apply(void *bias, const float *rsum, int32_t nrb, int64_t R, int32_t G, float lr, int dtype,
+                             hipStream_t st);
 struct BiasJob { void *bias; const void *dz; int64_t R, ld; int32_t blk0; };
 constexpr int kMaxBiasJobs = 16;
 struct BiasArgs { BiasJob job[kMaxBiasJobs]; int32_t njobs, B, G; float lr; };

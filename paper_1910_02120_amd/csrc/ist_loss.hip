@@ -5,29 +5,6 @@
 
 namespace ist {
 
-// 8 consecutive storage-type values as floats, from an address aligned to 16 bytes
-template <typename T> struct Row8T;
-template <> struct Row8T<uint16_t> {
-    __device__ static inline void ld(const uint16_t *p, float (&o)[8])
-    {
-        const uint4 r = *reinterpret_cast<const uint4 *>(p);
-        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            o[2 * i] = __uint_as_float(w[i] << 16);
-            o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-};
-template <> struct Row8T<float> {
-    __device__ static inline void ld(const float *p, float (&o)[8])
-    {
-        const float4 a = *reinterpret_cast<const float4 *>(p);
-        const float4 b = *reinterpret_cast<const float4 *>(p + 4);
-        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-    }
-};
-
 __device__ inline float wave_max(float v)
 {
 #pragma unroll
@@ -697,49 +674,29 @@ __global__ __launch_bounds__(256) void k_bias_update_wide(BiasJob jb, int32_t B,
     }
 }
 
-// Bias update of an output layer whose dz is stored transposed, dzt[g][r][ldb] (r = class, the B
-// samples of a class contiguous): bias[g][r] -= lr * sum_b dzt[g][r][b].  Eight lanes share a class
-// (each sums 8-element pieces 64 elements apart, then a fixed three-step tree), so a wave reads
-// 8 consecutive rows: contiguous memory when ldb <= 64.  Pad columns b >= B are skipped (they may hold
-// values of an earlier call with a larger batch).
+// Bias update of a wide output layer from the per-class partial sums that the dz pass left:
+// bias[g][r] -= lr * sum_blk rsum[(g * nrb + blk) * R + r], blocks in ascending order.
 template <typename D>
-__global__ __launch_bounds__(256) void k_bias_update_t(typename D::T *__restrict__ bias,
-                                                       const typename D::T *__restrict__ dzt, int64_t R, int64_t ldb,
-                                                       int32_t B, float lr)
+__global__ __launch_bounds__(256) void k_bias_apply(typename D::T *__restrict__ bias, const float *__restrict__ rsum,
+                                                    int32_t nrb, int64_t R, float lr)
 {
-    using T = typename D::T;
     const int g = blockIdx.y;
-    const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 3;
-    const int piece = threadIdx.x & 7;
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= R) return;
     float acc = 0.0f;
-    if (r < R) {
-        const T *row = dzt + ((int64_t)g * R + r) * ldb;
-        for (int64_t c = 8 * piece; c < ldb; c += 64) {
-            float v[8];
-            Row8T<T>::ld(row + c, v);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc += (c + i < B) ? v[i] : 0.0f;
-        }
-    }
-#pragma unroll
-    for (int o = 1; o < 8; o <<= 1) acc += __shfl_xor(acc, o);
-    if (r < R && piece == 0) {
-        T *b = bias + (int64_t)g * R + r;
-        *b = D::cvt(D::ld(b) - lr * acc);
-    }
+    for (int blk = 0; blk < nrb; ++blk) acc += rsum[((int64_t)g * nrb + blk) * R + r];
+    typename D::T *b = bias + (int64_t)g * R + r;
+    *b = D::cvt(D::ld(b) - lr * acc);
 }
 
-hipError_t launch_bias_update_t(void *bias, const void *dzt, int64_t R, int64_t ldb, int32_t B, int32_t G, float lr,
-                                int dtype, hipStream_t st)
+hipError_t launch_bias_apply(void *bias, const float *rsum, int32_t nrb, int64_t R, int32_t G, float lr, int dtype,
+                             hipStream_t st)
 {
-    if (ldb % 8 != 0 || reinterpret_cast<uintptr_t>(dzt) % 16 != 0) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((R * 8 + 255) / 256), (unsigned)G);
+    dim3 grid((unsigned)((R + 255) / 256), (unsigned)G);
     if (dtype == IST_BF16)
-        hipLaunchKernelGGL(k_bias_update_t<BF16>, grid, dim3(256), 0, st, static_cast<uint16_t *>(bias),
-                           static_cast<const uint16_t *>(dzt), R, ldb, B, lr);
+        hipLaunchKernelGGL(k_bias_apply<BF16>, grid, dim3(256), 0, st, static_cast<uint16_t *>(bias), rsum, nrb, R, lr);
     else
-        hipLaunchKernelGGL(k_bias_update_t<F32>, grid, dim3(256), 0, st, static_cast<float *>(bias),
-                           static_cast<const float *>(dzt), R, ldb, B, lr);
+        hipLaunchKernelGGL(k_bias_apply<F32>, grid, dim3(256), 0, st, static_cast<float *>(bias), rsum, nrb, R, lr);
     return hipGetLastError();
 }
 
