@@ -38,8 +38,10 @@ MEASURED_TRAFFIC = {
     # the three update products of a step in one launch:
     # read 74.85 MB (FETCH_SIZE 36547.1 KiB x 2.000) + written 34.13 MB (WRITE_SIZE 33328.0 KiB x 1.000)
     "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3": 108.98e6},
-    # read 1690.6 MB (825494.7 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000)
-    "cfg4": {"gemm_update_bf16_256x256_t512_persistent": 2585.3e6},
+    # read 1684.4 MB (822492.4 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000)
+    "cfg4": {"gemm_update_bf16_256x256_t512_persistent": 2579.2e6},
+    # second cross-entropy pass (dz^T): read 2840.2 MB (1386890.0 KiB x 2.000) + written 2839.0 MB (2772420.1 KiB x 1.000)
+    "cfg5": {"gemm_fwd_dzt_bf16_128x128_t256_persistent": 5679.2e6},
 }
 
 

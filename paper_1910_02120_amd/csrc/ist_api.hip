@@ -820,11 +820,12 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 a.C = sb + L.off_W; a.ldc = L.C; a.gC = L.R * L.C;
                 a.M = (int32_t)L.R; a.N = (int32_t)L.C; a.K = B; a.G = S;
                 a.lr = lr * ctx->scale[l - 1];   // dW_l = gamma_l dz_l^T h_{l-1}
-                upd.push_back(a);
+                // small products wait for the end of the backward chain and share a launch (they only need
+                // the dz_l, and nothing reads W_l any more in this step); the others go out now
+                if (gemm_update_shares_launch(dt, a)) upd.push_back(a);
+                else IST_RUN(KC_GEMM_UPDATE, launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
             }
         }
-        // The updates only need the dz_l (all final by now) and nothing reads W_l any more in this step:
-        // they go out together, small layers in one launch.
         for (size_t u0 = 0; u0 < upd.size(); u0 += 4) {
             const int nu = (int)std::min<size_t>(4, upd.size() - u0);
             IST_RUN(KC_GEMM_UPDATE, launch_gemm_updates(dt, upd.data() + u0, nu, st), "backward-weight gemm");

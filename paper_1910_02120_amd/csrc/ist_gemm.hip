@@ -140,6 +140,11 @@ hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, hipStream
     return hipSuccess;
 }
 
+bool gemm_update_shares_launch(int dtype, const GemmArgs &a)
+{
+    return !force_generic() && gemm_update_shares_launch_mfma(dtype, a);
+}
+
 int gemm_splits(int dtype, int epi, const GemmArgs &a)
 {
     return force_generic() ? 1 : gemm_splits_mfma(dtype, epi, a);

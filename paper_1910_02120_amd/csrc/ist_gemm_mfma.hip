@@ -1069,6 +1069,21 @@ int lse_block_width(int dtype, int32_t M, int32_t N, int32_t K, int32_t G)
 // The update products of several layers.  Those that take the small persistent 64x64 kernel with 16-byte
 // operand loads (every layer of the small f32 configurations) share one launch; any other goes out alone
 // (sharing a launch among 128x128-block products was measured and gains nothing: they already fill the chip).
+static bool update_shares_launch(const GemmArgs &a, int esz)
+{
+    if (a.M <= 0 || a.N <= 0 || a.G <= 0) return false;
+    const bool layout = a.sam == 1 && a.sbn == 1 && a.sak != 1 && a.sbk != 1;
+    const bool vec = vec_ok(a.A, a.gA, a.sak, esz) && vec_ok(a.B, a.gB, a.sbk, esz);
+    const SplitPlan p = plan_for(a, EPI_UPDATE, esz);
+    const int64_t total = (int64_t)((a.N + 63) / 64) * ((a.M + 63) / 64) * a.G;
+    return layout && vec && p.tile != 128 && total <= (1 << 20);
+}
+
+bool gemm_update_shares_launch_mfma(int dtype, const GemmArgs &a)
+{
+    return update_shares_launch(a, dtype == IST_BF16 ? 2 : 4);
+}
+
 template <typename D>
 static hipError_t launch_updates_typed(const GemmArgs *args, int n, hipStream_t st)
 {
@@ -1078,12 +1093,9 @@ static hipError_t launch_updates_typed(const GemmArgs *args, int n, hipStream_t 
     for (int i = 0; i < n; ++i) {
         const GemmArgs &a = args[i];
         if (a.M <= 0 || a.N <= 0 || a.G <= 0) continue;
-        const bool layout = a.sam == 1 && a.sbn == 1 && a.sak != 1 && a.sbk != 1;
-        const bool vec = vec_ok(a.A, a.gA, a.sak, esz) && vec_ok(a.B, a.gB, a.sbk, esz);
-        const SplitPlan p = plan_for(a, EPI_UPDATE, esz);
         const int tx = (a.N + 63) / 64, ty = (a.M + 63) / 64;
         const int64_t total = (int64_t)tx * ty * a.G;
-        if (!layout || !vec || p.tile == 128 || mm.n == kMaxMulti || total > (1 << 20)) {
+        if (!update_shares_launch(a, esz) || mm.n == kMaxMulti) {
             hipError_t e = launch_dtype<D>(EPI_UPDATE, a, st);
             if (e != hipSuccess) return e;
             continue;

@@ -205,6 +205,9 @@ hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a);
 // The EPI_UPDATE products of several layers (independent of each other); small ones share one launch.
+// gemm_update_shares_launch tells which do (the others are better launched, and timed, one by one).
+bool gemm_update_shares_launch(int dtype, const GemmArgs &a);
+bool gemm_update_shares_launch_mfma(int dtype, const GemmArgs &a);
 hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, hipStream_t st);
 hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, hipStream_t st);
 
