@@ -826,13 +826,27 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 else IST_RUN(KC_GEMM_UPDATE, launch_gemm(dt, EPI_UPDATE, a, st), "backward-weight gemm");
             }
         }
+        // narrow bias updates (they only need the dz_l of this step) ride along with the shared update launch
+        bool bias_done = false;
+        BiasArgs ride{};
+        if (ctx->has_bias && !ctx->fused_out && t <= kMaxBiasJobs && !upd.empty()) {
+            ride.B = B; ride.G = S; ride.lr = lr;
+            for (int l = 1; l <= t; ++l) {
+                const LayerPlan &L = ctx->layer[l - 1];
+                ride.job[ride.njobs++] = BiasJob{sb + L.off_b, ws + L.off_dz, L.R, L.ldr, 0};
+            }
+            if (!bias_jobs_all_narrow(ride, dt)) ride.njobs = 0;
+        }
         for (size_t u0 = 0; u0 < upd.size(); u0 += 4) {
             const int nu = (int)std::min<size_t>(4, upd.size() - u0);
-            IST_RUN(KC_GEMM_UPDATE, launch_gemm_updates(dt, upd.data() + u0, nu, st), "backward-weight gemm");
+            bool rode = false;
+            IST_RUN(KC_GEMM_UPDATE, launch_gemm_updates(dt, upd.data() + u0, nu, (ride.njobs && !bias_done) ? &ride : nullptr,
+                                                        &rode, st), "backward-weight gemm");
+            bias_done = bias_done || rode;
         }
         upd.clear();
         // all bias updates of the step in one launch (they only need the dz_l of this step)
-        if (ctx->has_bias) {
+        if (ctx->has_bias && !bias_done) {
             for (int l0 = 1; l0 <= t; l0 += kMaxBiasJobs) {
                 BiasArgs ba{};
                 ba.B = B; ba.G = S; ba.lr = lr;

@@ -130,9 +130,11 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
     return force_generic() ? launch_gemm_generic(dtype, epi, a, st) : launch_gemm_mfma(dtype, epi, a, st);
 }
 
-hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, hipStream_t st)
+hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
+                               hipStream_t st)
 {
-    if (!force_generic()) return launch_gemm_updates_mfma(dtype, args, n, st);
+    if (!force_generic()) return launch_gemm_updates_mfma(dtype, args, n, bias, bias_done, st);
+    if (bias_done) *bias_done = false;
     for (int i = 0; i < n; ++i) {
         hipError_t e = launch_gemm_generic(dtype, EPI_UPDATE, args[i], st);
         if (e != hipSuccess) return e;

@@ -25,6 +25,7 @@
 // The epilogue goes through LDS so that every lane owns 8 consecutive columns of a
 // row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses.
 #include "ist_internal.h"
+#include "ist_bias_block.h"
 
 #include <cstdio>
 
@@ -761,6 +762,10 @@ struct GemmMulti {
     int first[kMaxMulti + 1];
     int tiles_x[kMaxMulti], tiles_y[kMaxMulti], vecC[kMaxMulti];
     int n;
+    // optional: the bias updates of the same step (narrow layers), run by the workgroups after first[n]:
+    // bias_blocks column blocks for each of the bias.G subnets (bias_blocks == 0: none)
+    int bias_blocks;
+    BiasArgs bias;
 };
 
 template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
@@ -768,6 +773,11 @@ template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN
 __global__ IST_GEMM_BOUNDS
 void k_gemm_mfma_multi(GemmMulti mm)
 {
+    if ((int)blockIdx.x >= mm.first[mm.n]) {   // whole workgroups: the barrier inside is safe
+        const int e = (int)blockIdx.x - mm.first[mm.n];
+        bias_update_block<D>(mm.bias, e % mm.bias_blocks, e / mm.bias_blocks);
+        return;
+    }
     int i = 0;
     while (i + 1 < mm.n && (int)blockIdx.x >= mm.first[i + 1]) ++i;
     const GemmArgs a = mm.p[i];
@@ -1084,8 +1094,9 @@ bool gemm_update_shares_launch_mfma(int dtype, const GemmArgs &a)
     return update_shares_launch(a, dtype == IST_BF16 ? 2 : 4);
 }
 
+// bias (optional): the narrow bias updates of the step; *bias_done tells whether they rode along
 template <typename D>
-static hipError_t launch_updates_typed(const GemmArgs *args, int n, hipStream_t st)
+static hipError_t launch_updates_typed(const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done, hipStream_t st)
 {
     const int esz = D::kBytes;
     GemmMulti mm{};
@@ -1109,20 +1120,39 @@ static hipError_t launch_updates_typed(const GemmArgs *args, int n, hipStream_t 
         ++mm.n;
     }
     if (mm.n == 0) return hipGetLastError();
-    if (mm.n == 1) return launch_dtype<D>(EPI_UPDATE, mm.p[0], st);
+    const bool ride = bias && bias->njobs > 0 && bias->G > 0;
+    if (mm.n == 1 && !ride) return launch_dtype<D>(EPI_UPDATE, mm.p[0], st);
+    int64_t grid = mm.first[mm.n];
+    if (bias && bias->njobs > 0 && bias->G > 0) {
+        mm.bias = *bias;
+        int blocks = 0;
+        for (int j = 0; j < mm.bias.njobs; ++j) {
+            mm.bias.job[j].blk0 = blocks;
+            blocks += (int)((mm.bias.job[j].R + 63) / 64);
+        }
+        if (blocks > 0 && (int64_t)blocks * mm.bias.G < (1 << 20)) {
+            mm.bias_blocks = blocks;
+            grid += (int64_t)blocks * mm.bias.G;
+            if (bias_done) *bias_done = true;
+        }
+    }
     char label[64];
-    snprintf(label, sizeof(label), "gemm_update_%s_64x64_t256_persistent_x%d", esz == 2 ? "bf16" : "f32", mm.n);
+    snprintf(label, sizeof(label), "gemm_update_%s_64x64_t256_persistent_x%d%s", esz == 2 ? "bf16" : "f32", mm.n,
+             mm.bias_blocks ? "_bias" : "");
     tag_kernel(label, flops, 0.0);
-    hipLaunchKernelGGL((k_gemm_mfma_multi<D, false, false, EPI_UPDATE, 64, 64, 2, 2, 1, 3, true, 32>), dim3((unsigned)mm.first[mm.n]),
+    hipLaunchKernelGGL((k_gemm_mfma_multi<D, false, false, EPI_UPDATE, 64, 64, 2, 2, 1, 3, true, 32>), dim3((unsigned)grid),
                        dim3(256), 0, st, mm);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, hipStream_t st)
+hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
+                                    hipStream_t st)
 {
+    if (bias_done) *bias_done = false;
     for (int i = 0; i < n; ++i)
         if (args[i].zeros == nullptr) return hipErrorInvalidValue;
-    return dtype == IST_BF16 ? launch_updates_typed<BF16>(args, n, st) : launch_updates_typed<F32>(args, n, st);
+    return dtype == IST_BF16 ? launch_updates_typed<BF16>(args, n, bias, bias_done, st)
+                             : launch_updates_typed<F32>(args, n, bias, bias_done, st);
 }
 
 hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st)

@@ -208,8 +208,6 @@ int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a);
 // gemm_update_shares_launch tells which do (the others are better launched, and timed, one by one).
 bool gemm_update_shares_launch(int dtype, const GemmArgs &a);
 bool gemm_update_shares_launch_mfma(int dtype, const GemmArgs &a);
-hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, hipStream_t st);
-hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, hipStream_t st);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
@@ -241,6 +239,13 @@ struct BiasJob { void *bias; const void *dz; int64_t R, ld; int32_t blk0; };
 constexpr int kMaxBiasJobs = 16;
 struct BiasArgs { BiasJob job[kMaxBiasJobs]; int32_t njobs, B, G; float lr; };
 hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st);
+// true if every job of `a` takes the narrow kernel (so that the jobs can ride along with another launch)
+bool bias_jobs_all_narrow(const BiasArgs &a, int dtype);
+// `bias` (optional): narrow bias updates of the same step; *bias_done = they were done inside the shared launch
+hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
+                               hipStream_t st);
+hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
+                                    hipStream_t st);
 
 // sparse-input first layer (weights stored [G][N0][w])
 struct CsrArgs {

@@ -2,6 +2,7 @@
 // the local SGD step (Section 2.1 "Training Subnets"; loss of equation (1) taken
 // as the mean softmax cross-entropy over the mini-batch).
 #include "ist_internal.h"
+#include "ist_bias_block.h"
 
 namespace ist {
 
@@ -571,39 +572,10 @@ hipError_t launch_norm_backward(void *dz, const void *zh, const float *isg, int3
     return hipGetLastError();
 }
 
-// b_l[g][r] <- b_l[g][r] - lr * sum_b dz_l[g][b][r] for several layers in one launch.
-// A workgroup owns 64 columns of one (layer, subnet); its 4 wavefronts split the
-// batch rows, partial sums meet in LDS, summation order is fixed.
 template <typename D>
 __global__ __launch_bounds__(256) void k_bias_update(BiasArgs a)
 {
-    using T = typename D::T;
-    __shared__ float part[4][64];
-    int j = 0;
-    while (j + 1 < a.njobs && (int)blockIdx.x >= a.job[j + 1].blk0) ++j;
-    const BiasJob jb = a.job[j];
-    const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t r = (int64_t)(blockIdx.x - jb.blk0) * 64 + lane;
-    float acc = 0.0f;
-    if (r < jb.R) {
-        const T *p = static_cast<const T *>(jb.dz) + (int64_t)g * a.B * jb.ld + r;
-        int b = wave;
-        for (; b + 28 < a.B; b += 32) {   // 8 rows in flight per wave; the order of the sum stays b ascending
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = D::ld(p + (int64_t)(b + 4 * u) * jb.ld);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
-        }
-        for (; b < a.B; b += 4) acc += D::ld(p + (int64_t)b * jb.ld);
-    }
-    part[wave][lane] = acc;
-    __syncthreads();
-    if (wave == 0 && r < jb.R) {
-        float tot = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
-        T *w = static_cast<T *>(jb.bias) + (int64_t)g * jb.R + r;
-        *w = D::cvt(D::up(*w) - a.lr * tot);
-    }
+    bias_update_block<D>(a, (int)blockIdx.x, (int)blockIdx.y);
 }
 
 // Wide layers: a workgroup owns 512 columns (8 per lane, one 16-byte load per lane and row), its
@@ -700,16 +672,27 @@ hipError_t launch_bias_apply(void *bias, const float *rsum, int32_t nrb, int64_t
     return hipGetLastError();
 }
 
+static bool bias_job_wide(const BiasJob &jb, int32_t B, int dtype)
+{
+    const int che = dtype == IST_BF16 ? 8 : 4;
+    return jb.R >= 2048 && jb.ld % 8 == 0 && reinterpret_cast<uintptr_t>(jb.dz) % 16 == 0 && ((int64_t)B * jb.ld) % che == 0;
+}
+
+bool bias_jobs_all_narrow(const BiasArgs &a, int dtype)
+{
+    for (int j = 0; j < a.njobs; ++j)
+        if (bias_job_wide(a.job[j], a.B, dtype)) return false;
+    return true;
+}
+
 hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st)
 {
     if (a.njobs <= 0) return hipSuccess;
     // wide layers go to the 16-byte kernel, one launch each; the rest share one launch
-    const int che = dtype == IST_BF16 ? 8 : 4;
     int kept = 0;
     for (int j = 0; j < a.njobs; ++j) {
         const BiasJob &jb = a.job[j];
-        const bool wide = jb.R >= 2048 && jb.ld % 8 == 0 && reinterpret_cast<uintptr_t>(jb.dz) % 16 == 0 &&
-                          ((int64_t)a.B * jb.ld) % che == 0;
+        const bool wide = bias_job_wide(jb, a.B, dtype);
         if (!wide) { a.job[kept++] = jb; continue; }
         dim3 grid((unsigned)((jb.ld + 511) / 512), (unsigned)a.G);
         if (dtype == IST_BF16)
