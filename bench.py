@@ -35,9 +35,9 @@ EVENT_OVERHEAD_US = 2.4
 # (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the 1 GiB copy of
 # --calibrate-copy; the runs and the scale factors are in profiles/.  {workload: {kernel label: bytes}}
 MEASURED_TRAFFIC = {
-    # the three update products of a step in one launch:
-    # read 74.85 MB (FETCH_SIZE 36547.1 KiB x 2.000) + written 34.13 MB (WRITE_SIZE 33328.0 KiB x 1.000)
-    "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3": 108.98e6},
+    # the three update products of a step and their bias updates in one launch:
+    # read 77.05 MB (FETCH_SIZE 37621.5 KiB x 2.000) + written 34.16 MB (WRITE_SIZE 33360.7 KiB x 1.000)
+    "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3_bias": 111.21e6},
     # read 1684.4 MB (822492.4 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000)
     "cfg4": {"gemm_update_bf16_256x256_t512_persistent": 2579.2e6},
     # second cross-entropy pass (dz^T): read 2840.2 MB (1386890.0 KiB x 2.000) + written 2839.0 MB (2772420.1 KiB x 1.000)
