@@ -1,6 +1,6 @@
 // MFMA grouped GEMM for the subnet SGD step (gfx950).
 //
-//   C_g[m][n] = sum_k A_g(m,k) * B_g(n,k),   g = subnet (blockIdx.z)
+//   C_g[m][n] = sum_k A_g(m,k) * B_g(n,k),   g = subnet (part of the 1-D tile index)
 //
 // Each operand is either K-contiguous (rows of k values) or M-contiguous (the
 // matrix is stored with k as the slow index).  The three products of a layer
@@ -8,7 +8,9 @@
 //   forward         A = h_{l-1} (K-contig)   B = W_l (K-contig)
 //   backward data   A = dz_l    (K-contig)   B = W_l (M-contig: k runs over rows of W_l)
 //   backward weight A = dz_l    (M-contig)   B = h_{l-1} (M-contig)
-// so no operand is ever stored twice or transposed in memory.
+// so no operand is ever stored twice or transposed in memory.  A wide output layer keeps its
+// dz transposed (classes x samples, written by the second cross-entropy pass); there the
+// backward-data product reads A M-contiguous and the update reads it K-contiguous.
 //
 // bf16: v_mfma_f32_32x32x16_bf16.  K-contiguous tiles sit in LDS as [row][k] and a
 // lane's 8 consecutive k values are one 128-bit LDS read; M-contiguous tiles sit as
@@ -23,7 +25,9 @@
 // 64x64 tiles with KG > 1 so that all SIMDs have a wave; large ones 128x128, KG = 1.
 // Global loads are 16 bytes per lane and run ST k-tiles ahead in registers.
 // The epilogue goes through LDS so that every lane owns 8 consecutive columns of a
-// row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses.
+// row: bias/ReLU, the ReLU mask, or the in-place SGD update then use 16-byte accesses
+// (the row statistics of a wide output layer are taken from the accumulators directly).
+// The update products of several small layers, and their bias updates, can share one launch.
 #include "ist_internal.h"
 #include "ist_bias_block.h"
 
