@@ -81,14 +81,23 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
 {
     using T = typename D::T;
     const int lane = threadIdx.x & 63;
-    const int64_t wid = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (wid >= (int64_t)c.G * c.N0) return;
+    // a wavefront looks at 64 (group, column) pairs at once - most columns do not occur in a batch -
+    // and then works through the ones that do, one after the other
+    const int64_t w0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
+    const int64_t total = (int64_t)c.G * c.N0;
+    if (w0 >= total) return;
+    bool mine = false;
+    if (w0 + lane < total) {
+        const uint32_t *b0 = bitmap + (w0 + lane) * words;
+        for (int i = 0; i < words; ++i) mine |= (b0[i] != 0u);
+    }
+    unsigned long long present = __ballot(mine);
+    while (present) {
+    const int64_t wid = w0 + (__ffsll((long long)present) - 1);
+    present &= present - 1;
     const int g = (int)(wid / c.N0);
     const int32_t col = (int32_t)(wid % c.N0);
     const uint32_t *bm = bitmap + wid * words;
-    bool any = false;
-    for (int i = lane; i < words; i += 64) any |= (bm[i] != 0u);
-    if (__ballot(any) == 0ull) return;
 
     const T *vals = static_cast<const T *>(c.vals);
     T *wrow = Wt + ((int64_t)g * c.N0 + col) * c.w;
@@ -131,6 +140,7 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
             if (q < c.w) wrow[q] = D::cvt(D::up(wrow[q]) - lr * acc[i]);
         }
     }
+    }
 }
 
 hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out, int dtype,
@@ -164,7 +174,7 @@ hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_
     hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, st, bitmap, nwords, 0u);
     hipLaunchKernelGGL(k_csr_mark, dim3((unsigned)c.B, (unsigned)c.G), dim3(256), 0, st, c, bitmap,
                        words);
-    const int64_t waves = (int64_t)c.G * c.N0;
+    const int64_t waves = ((int64_t)c.G * c.N0 + 63) / 64;   // 64 (group, column) pairs per wavefront
     dim3 grid((unsigned)((waves + 3) / 4));
     if (dtype == IST_BF16)
         hipLaunchKernelGGL(k_csr_update<BF16>, grid, dim3(256), 0, st, c, (uint16_t *)Wt,
