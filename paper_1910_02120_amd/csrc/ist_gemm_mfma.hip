@@ -985,8 +985,17 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
             }
         }
         if constexpr (D::kBytes == 2 && EPI == EPI_UPDATE) {
+            // a wide layer with at most 128 columns per subnet (a wide output layer): 256x128 blocks, so that no
+            // MFMA work is spent on columns that do not exist
+            if (a.N <= 128 && a.K >= 128 && (int64_t)((a.M + 255) / 256) * a.G >= 1024) {
+                launch_tiles<256, 128>(k_gemm_mfma<D, AK, BKC, EPI, 256, 128, 2, 2, 1, 1, VEC, 64, true, false>, 256, a, vecC,
+                                       1, a.K, st, true, 512);
+                done = true;
+            }
+        }
+        if constexpr (D::kBytes == 2 && EPI == EPI_UPDATE) {
             // wide layers: one persistent 256x256 workgroup per CU, started in 4 phase groups
-            if (a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
+            if (!done && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
                 launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, true, true>, 512, a, vecC,
                                        1, a.K, st, true, 256, 4, 1);
                 done = true;
