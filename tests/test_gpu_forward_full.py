@@ -143,3 +143,30 @@ def test_wide_stress_size_against_library_matmul():
     err = float((got - h).abs().max()) / float(h.abs().max())
     assert err <= H.TOL[cfg.dtype], err
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "ragged-bf16", "csr-f32"])
+def test_round_then_full_forward_matches_oracle_end_to_end(name):
+    """partition -> k local steps -> merge on the GPU, then the logits of the merged network, against the
+    oracle's round followed by its full forward pass: every entry point of a round in one chain."""
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, dev="cuda:0")
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    P.gpu_steps(ctx, loss=False)
+    ctx.merge(P.dW, P.db)
+    got = ctx.forward_full(P.dW, P.db, cfg.B, X=P.dX, csr=P.dcsr)
+    torch.cuda.synchronize()
+    Ws = [w.copy() for w in P.Ws]
+    bs = [b.copy() for b in P.bs]
+    if cfg.input == "csr":
+        orc.ist_round(Ws, bs, P.perms, cfg.S, cfg.lr, cfg.k, cfg.dtype, P.y,
+                      csr=(P.rp, P.ci, P.va.astype(np.float64)))
+        rp, ci, va = orc.csr_slice(P.rp, P.ci, P.va, 0, cfg.B)
+        want = orc.forward_full(Ws, bs, cfg.dtype, csr=(rp, ci, va.astype(np.float64)))
+    else:
+        orc.ist_round(Ws, bs, P.perms, cfg.S, cfg.lr, cfg.k, cfg.dtype, P.y, X=P.X)
+        want = orc.forward_full(Ws, bs, cfg.dtype, X=P.X.reshape(-1, cfg.dims[0])[:cfg.B])
+    err = float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - want))) / float(np.max(np.abs(want)))
+    assert err <= 2 * H.TOL[cfg.dtype], (name, err)
+    ctx.close()
