@@ -459,20 +459,18 @@ ist_status ist_partition(ist_ctx *ctx, const ist_params *params, const int32_t *
     ist_status ts = build_tables(ctx, ctx->subnets, perm, st, "ist_partition");
     if (ts != IST_OK) return ts;
 
+    BiasCopyJobs bj{};
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
         CopyArgs a = copy_args(ctx, ctx->subnets, l, params->W[l - 1]);
         IST_RUN(KC_PARTITION_COPY, launch_partition_copy(a, st), "partition copy");
-        if (ctx->has_bias) {
-            if (l < t) {
-                IST_RUN(KC_BIAS_COPY, launch_bias_rows(params->b[l - 1], ctx->subnets + L.off_b, a.rows, L.R * S, e, false, st),
-                        "partition bias");
-            } else {
-                IST_RUN(KC_BIAS_COPY, launch_bias_replicate(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, e, st),
-                        "replicate output bias");
-            }
+        if (ctx->has_bias) {   // hidden biases travel with their neuron, the output bias goes to every subnet
+            if (bj.njobs == 16) { IST_RUN(KC_BIAS_COPY, launch_bias_jobs(bj, e, false, st), "partition biases"); bj.njobs = 0; }
+            if (l < t) bj.job[bj.njobs++] = BiasCopyJob{params->b[l - 1], ctx->subnets + L.off_b, a.rows, L.R * S, S, 0};
+            else bj.job[bj.njobs++] = BiasCopyJob{params->b[l - 1], ctx->subnets + L.off_b, nullptr, L.R, S, 0};
         }
     }
+    if (bj.njobs) IST_RUN(KC_BIAS_COPY, launch_bias_jobs(bj, e, false, st), "partition biases");
     ctx->partitioned = true;
     return IST_OK;
 }
@@ -485,20 +483,22 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream)
     if (ps != IST_OK) return ps;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int t = ctx->t, S = ctx->S, e = ctx->esz();
+    BiasCopyJobs bj{};
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
         CopyArgs a = copy_args(ctx, ctx->subnets, l, params->W[l - 1]);
         IST_RUN(KC_MERGE_COPY, launch_merge_copy(a, st), "merge copy");
         if (ctx->has_bias) {
             if (l < t) {
-                IST_RUN(KC_BIAS_COPY, launch_bias_rows(params->b[l - 1], ctx->subnets + L.off_b, a.rows, L.R * S, e, true, st),
-                        "merge bias");
+                if (bj.njobs == 16) { IST_RUN(KC_BIAS_COPY, launch_bias_jobs(bj, e, true, st), "merge biases"); bj.njobs = 0; }
+                bj.job[bj.njobs++] = BiasCopyJob{params->b[l - 1], ctx->subnets + L.off_b, a.rows, L.R * S, S, 0};
             } else {
                 IST_RUN(KC_BIAS_COPY, launch_bias_mean(params->b[l - 1], ctx->subnets + L.off_b, L.R, S, ctx->dtype, st),
                         "mean output bias");
             }
         }
     }
+    if (bj.njobs) IST_RUN(KC_BIAS_COPY, launch_bias_jobs(bj, e, true, st), "merge biases");
     return IST_OK;
 }
 

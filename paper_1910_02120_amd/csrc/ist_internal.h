@@ -143,6 +143,10 @@ struct CopyArgs {
 hipError_t launch_partition_copy(const CopyArgs &a, hipStream_t st);
 hipError_t launch_merge_copy(const CopyArgs &a, hipStream_t st);
 hipError_t launch_resample_copy(const CopyArgs &old_part, const CopyArgs &new_part, bool *fused, hipStream_t st);
+// bias copies of several layers in one launch (partition: gather / replicate; merge: scatter of the hidden layers)
+struct BiasCopyJob { void *b; void *sub; const int32_t *rows; int64_t n; int32_t G; int32_t blk0; };
+struct BiasCopyJobs { BiasCopyJob job[16]; int32_t njobs; };
+hipError_t launch_bias_jobs(BiasCopyJobs &a, int esz, bool scatter, hipStream_t st);
 hipError_t launch_bias_rows(void *b, void *sub, const int32_t *rows, int64_t n, int esz, bool scatter,
                             hipStream_t st);
 hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G, int esz,

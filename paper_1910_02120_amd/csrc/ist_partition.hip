@@ -734,6 +734,44 @@ hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G,
     return hipGetLastError();
 }
 
+// The bias copies of all layers of one phase in one launch: per job either sub[P] <-> b[rows[P]] (hidden
+// layers, n = S * w values) or the replication of the n output biases to the G subnets (rows == null).
+template <typename E, bool SCATTER>
+__global__ __launch_bounds__(256) void k_bias_jobs(BiasCopyJobs a)
+{
+    int j = 0;
+    while (j + 1 < a.njobs && (int)blockIdx.x >= a.job[j + 1].blk0) ++j;
+    const BiasCopyJob jb = a.job[j];
+    const int64_t i = (int64_t)(blockIdx.x - jb.blk0) * 256 + threadIdx.x;
+    if (i >= jb.n) return;
+    E *b = static_cast<E *>(jb.b), *sub = static_cast<E *>(jb.sub);
+    if (jb.rows) {
+        if (SCATTER) b[jb.rows[i]] = sub[i]; else sub[i] = b[jb.rows[i]];
+    } else if (!SCATTER) {
+        const E v = b[i];
+        for (int g = 0; g < jb.G; ++g) sub[(int64_t)g * jb.n + i] = v;
+    }
+}
+
+hipError_t launch_bias_jobs(BiasCopyJobs &a, int esz, bool scatter, hipStream_t st)
+{
+    int blocks = 0;
+    for (int j = 0; j < a.njobs; ++j) {
+        a.job[j].blk0 = blocks;
+        blocks += (int)((a.job[j].n + 255) / 256);
+    }
+    if (blocks == 0) return hipSuccess;
+    const dim3 grid((unsigned)blocks);
+    if (esz == 2) {
+        if (scatter) hipLaunchKernelGGL((k_bias_jobs<uint16_t, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((k_bias_jobs<uint16_t, false>), grid, dim3(256), 0, st, a);
+    } else {
+        if (scatter) hipLaunchKernelGGL((k_bias_jobs<uint32_t, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((k_bias_jobs<uint32_t, false>), grid, dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_bias_mean(void *b, const void *sub, int64_t n, int32_t G, int dtype,
                             hipStream_t st)
 {
