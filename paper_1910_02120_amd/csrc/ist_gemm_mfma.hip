@@ -901,7 +901,7 @@ SplitPlan plan_gemm(int32_t M, int32_t N, int32_t K, int32_t G, bool allow_split
 // Per-dtype parameters: k-tile sizes, k-groups of the small configurations.
 template <typename D> struct Cfg;
 template <> struct Cfg<F32> { static constexpr int KG64 = 4, KG32 = 4, KT_SMALL = 64, KT_BIG = 32, ST_BIG = 2; };
-template <> struct Cfg<BF16> { static constexpr int KG64 = 4, KG32 = 4, KT_SMALL = 64, KT_BIG = 64, ST_BIG = 1; };
+template <> struct Cfg<BF16> { static constexpr int KG64 = 2, KG32 = 4, KT_SMALL = 64, KT_BIG = 64, ST_BIG = 1; };
 
 // 1-D grid over block tiles.  With many more tiles than the chip holds at once the grid is
 // capped and every workgroup walks several tiles (prefetching across them); otherwise one
