@@ -52,6 +52,8 @@ SHAPES = {
     # wide output layer with a full 256-row batch: the row-statistics pass takes its 256x256 blocks
     "wide-out-bf16-B256": _mk("wide-out-bf16-B256", "cfg5", dims=(200, 512, 33001), S=8, B=256, k=2,
                               nnz_per_row=10, lr=0.5),
+    # more layers than one bias launch, one bias-copy launch or one shared update launch takes (16 / 16 / 4)
+    "very-deep-f32": _mk("very-deep-f32", "cfg2", dims=(16,) + (32,) * 18 + (5,), S=2, B=6, k=2, lr=0.05),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
 }
