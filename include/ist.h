@@ -156,7 +156,8 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream);
  * writes is the row partition would read back.  The new blocks are built in a second
  * subnet buffer given once with ist_bind_spare (same size and alignment as `subnets` of
  * ist_bind, caller-owned device memory, must stay valid while the context is used); the
- * two buffers change roles at every call.  IST_ESTATE before ist_partition or without a
+ * two buffers change roles at every call; ist_bind forgets the spare (give it again after a
+ * re-bind).  IST_ESTATE before ist_partition or without a
  * spare buffer; with checking on, a perm that is not a permutation gives IST_EPERM and
  * leaves `params` and the current subnets untouched.
  */
@@ -208,7 +209,9 @@ const char *ist_profile_class_name(int32_t kernel_class);
  * ist_profile_kernel copies entry `index`: its label (NUL-terminated, truncated to
  * label_cap), its kernel class, the summed kernel time [ms], the number of launches,
  * and the algorithmic work summed over those launches: flops (2*M*N*K per product
- * and subnet; 0 for copy kernels) and bytes (copy kernels: the cache-line-granular
+ * and subnet; 0 for copy kernels) and bytes (products: every operand element read
+ * once, every result written once, the weights of an update read and written, the
+ * ReLU mask of a backward-data product read; copy kernels: the cache-line-granular
  * minimum - rows a block touches are read whole, and rewritten whole on merge when
  * their columns are partitioned; 0 where not tracked).  All pointers [host].
  */

@@ -39,6 +39,7 @@ class ISTConfig:
     lr: float = 0.01
     nnz_per_row: int = 75         # CSR only
     label_dist: str = "teacher"   # "teacher" | "zipf"
+    init_gain: float = 1.0        # multiplies the Xavier bound of the initial weights
 
     @property
     def t(self) -> int:
@@ -110,7 +111,7 @@ def make_weights(cfg: ISTConfig, with_bias: bool = True, bias_scale: float = 0.0
     Ws, bs = [], []
     for l in range(1, cfg.t + 1):
         fan_out, fan_in = cfg.dims[l], cfg.dims[l - 1]
-        a = np.sqrt(6.0 / (fan_in + fan_out))
+        a = cfg.init_gain * np.sqrt(6.0 / (fan_in + fan_out))
         W = g.uniform(-a, a, size=(fan_out, fan_in)).astype(np.float32)
         Ws.append(quantize(W, cfg.dtype))
         if with_bias:

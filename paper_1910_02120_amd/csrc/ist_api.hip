@@ -288,12 +288,10 @@ ist_status ist_profile_read(ist_ctx *ctx, int32_t cls, double *total_ms, int64_t
     double tot = 0.0;
     int64_t n = 0;
     if (!ctx->prof_recs.empty()) IST_HIP(hipEventSynchronize(ctx->prof_recs.back().stop), "profile read");
-    static const bool dump = getenv("IST_PROF_DUMP") != nullptr;   // debugging aid: one line per launch
     for (auto &r : ctx->prof_recs) {
         if (r.cls != cls) continue;
         float ms = 0.0f;
         IST_HIP(hipEventElapsedTime(&ms, r.start, r.stop), "profile read");
-        if (dump) fprintf(stderr, "ist_prof %s %.2f us\n", kClassNames[cls], ms * 1e3);
         tot += ms;
         ++n;
     }
@@ -369,6 +367,7 @@ ist_status ist_bind(ist_ctx *ctx, void *subnets, size_t sb, void *workspace, siz
     ctx->subnets = static_cast<char *>(subnets);
     ctx->workspace = static_cast<char *>(workspace);
     ctx->partitioned = false;
+    ctx->spare = nullptr;   // a spare bound earlier may be the buffer bound now: ask for it again
     // Index tables start as zeros so that they hold in-range values at all times,
     // also after a partition with an invalid permutation.
     const size_t tables = ctx->layer[0].off_W;
@@ -414,10 +413,11 @@ static ist_status build_tables(ist_ctx *ctx, char *base, const int32_t *const *p
 {
     const int t = ctx->t, S = ctx->S;
     if (ctx->checked) {
-        IST_HIP(hipMemsetAsync(ctx->errflag(), 0, sizeof(int32_t), st), "clear flag");
+        // fills by a kernel, not memset nodes, so that a caller may record the call into a HIP graph
+        IST_HIP(launch_fill_u32(ctx->errflag(), 1, 0u, st), "clear flag");
         for (int l = 1; l < t; ++l)
-            IST_HIP(hipMemsetAsync(ctx->workspace + ctx->hidden[l - 1].off_invpos, 0xff,
-                                   sizeof(int32_t) * ctx->hidden[l - 1].N, st), "clear invpos");
+            IST_HIP(launch_fill_u32(ctx->workspace + ctx->hidden[l - 1].off_invpos, ctx->hidden[l - 1].N, 0xffffffffu, st),
+                    "clear invpos");
     }
     for (int l = 1; l < t; ++l) {
         const HiddenPlan &h = ctx->hidden[l - 1];
@@ -579,59 +579,97 @@ ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, voi
     return IST_OK;
 }
 
-ist_status ist_forward_full(ist_ctx *ctx, const ist_params *params, const ist_batch *bt, float *logits, void *stream)
+// Where the full-network forward pass keeps its intermediate values: either regions of the bound
+// workspace or a layout inside the library's own static scratch array.
+struct FullFwdBuffers {
+    char *act[64], *z[64], *zh[64], *isg[64];   // per layer l-1 (hidden layers; z / zh / isg with normalize only)
+    int64_t pitch[64];                          // row pitch of layer l's activations, in elements
+    float *partial; size_t partial_bytes;       // split-K scratch
+    const void *zeros;                          // 256 zero bytes
+};
+
+static ist_status forward_full_checks(ist_ctx *ctx, const ist_params *params, const ist_batch *bt, float *logits,
+                                      const char *who)
 {
-    if (!ctx) return IST_EINVAL;
-    if (!ctx->bound) return fail(ctx, IST_ESTATE, "ist_forward_full: call ist_bind first");
-    if (!params || !params->W || !bt || !logits) return fail(ctx, IST_EINVAL, "ist_forward_full: null argument");
-    if (ctx->has_bias && !params->b) return fail(ctx, IST_EINVAL, "ist_forward_full: null bias list");
-    if (bt->B < 1 || bt->B > ctx->max_B) return fail(ctx, IST_ESHAPE, "ist_forward_full: B outside 1..max_B");
-    const bool csr = ctx->input == IST_CSR;
-    if (csr) {
+    if (!params || !params->W || !bt || !logits) return fail(ctx, IST_EINVAL, std::string(who) + ": null argument");
+    if (ctx->has_bias && !params->b) return fail(ctx, IST_EINVAL, std::string(who) + ": null bias list");
+    if (bt->B < 1 || bt->B > ctx->max_B) return fail(ctx, IST_ESHAPE, std::string(who) + ": B outside 1..max_B");
+    if (ctx->input == IST_CSR) {
         if (!bt->rowptr || !bt->colidx || !bt->vals || bt->nnz < 0)
-            return fail(ctx, IST_EINVAL, "ist_forward_full: incomplete CSR batch");
+            return fail(ctx, IST_EINVAL, std::string(who) + ": incomplete CSR batch");
     } else if (!bt->x) {
-        return fail(ctx, IST_EINVAL, "ist_forward_full: null x");
+        return fail(ctx, IST_EINVAL, std::string(who) + ": null x");
     }
-    const int t = ctx->t, S = ctx->S, B = bt->B, dt = ctx->dtype;
-    for (int l = 1; l <= t; ++l)
+    for (int l = 1; l <= ctx->t; ++l)
         if (!params->W[l - 1] || (ctx->has_bias && !params->b[l - 1]))
-            return fail(ctx, IST_EINVAL, "ist_forward_full: null parameter array");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    char *ws = ctx->workspace;
-    // One group of full width: the activation regions hold S subnets of max_B x ldr each, which is
-    // exactly room for max_B rows of S * ldr >= N_l values.
-    auto pitch = [&](int l) { return (int64_t)S * ctx->layer[l - 1].ldr; };
+            return fail(ctx, IST_EINVAL, std::string(who) + ": null parameter array");
+    if (ctx->t > 64) return fail(ctx, IST_EUNSUPPORTED, std::string(who) + ": more than 64 layers");
+    return IST_OK;
+}
+
+static ist_status forward_full_run(ist_ctx *ctx, const ist_params *params, const ist_batch *bt, float *logits,
+                                   const FullFwdBuffers &fb, hipStream_t st)
+{
+    const bool csr = ctx->input == IST_CSR;
+    const int t = ctx->t, B = bt->B, dt = ctx->dtype;
     for (int l = 1; l <= t; ++l) {
         const LayerPlan &L = ctx->layer[l - 1];
         const void *bias = ctx->has_bias ? params->b[l - 1] : nullptr;
         const bool nrm = ctx->normalize && l < t;
         if (l == 1 && csr) {
-            CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, 0, 0, 1, B, L.N_in, L.N_out, pitch(1)};
-            IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, params->W[0], bias, ws + L.off_act,
-                                       nrm ? reinterpret_cast<float *>(ws + L.off_z) : nullptr, dt, st, true),
+            CsrArgs c{bt->rowptr, bt->colidx, bt->vals, bt->nnz, 0, 0, 1, B, L.N_in, L.N_out, fb.pitch[0]};
+            IST_RUN(KC_CSR_FORWARD, launch_csr_forward(c, params->W[0], bias, fb.act[0],
+                                       nrm ? reinterpret_cast<float *>(fb.z[0]) : nullptr, dt, st, true),
                     "csr forward (full network)");
         } else {
             GemmArgs a{};
-            set_split(ctx, a);
+            a.partial = fb.partial_bytes ? fb.partial : nullptr;
+            a.partial_bytes = fb.partial_bytes;
+            a.zeros = fb.zeros;
             if (l == 1) { a.A = bt->x; a.sam = L.N_in; }
-            else { a.A = ws + ctx->layer[l - 2].off_act; a.sam = pitch(l - 1); }
+            else { a.A = fb.act[l - 2]; a.sam = fb.pitch[l - 2]; }
             a.sak = 1; a.gA = 0;
             a.B = params->W[l - 1]; a.sbn = L.N_in; a.sbk = 1; a.gB = 0;
             a.M = B; a.N = (int32_t)L.N_out; a.K = (int32_t)L.N_in; a.G = 1;
             a.bias = bias; a.gBias = 0;
             if (l == t) { a.C = logits; a.ldc = L.N_out; }
-            else if (nrm) { a.C = ws + L.off_z; a.ldc = pitch(l); }
-            else { a.C = ws + L.off_act; a.ldc = pitch(l); }
+            else if (nrm) { a.C = fb.z[l - 1]; a.ldc = fb.pitch[l - 1]; }
+            else { a.C = fb.act[l - 1]; a.ldc = fb.pitch[l - 1]; }
             a.gC = 0;
             IST_RUN(KC_GEMM_FWD, launch_gemm(dt, (l == t || nrm) ? EPI_FWD_LOGITS : EPI_FWD_RELU, a, st),
                     "forward gemm (full network)");
         }
         if (nrm)
-            IST_RUN(KC_NORM, launch_norm_forward(reinterpret_cast<const float *>(ws + L.off_z), ws + L.off_zh,
-                                ws + L.off_act, reinterpret_cast<float *>(ws + L.off_isg), 1, B, L.N_out, pitch(l),
+            IST_RUN(KC_NORM, launch_norm_forward(reinterpret_cast<const float *>(fb.z[l - 1]), fb.zh[l - 1],
+                                fb.act[l - 1], reinterpret_cast<float *>(fb.isg[l - 1]), 1, B, L.N_out, fb.pitch[l - 1],
                                 ctx->norm_eps, dt, st), "standardise (full network)");
     }
+    return IST_OK;
+}
+
+ist_status ist_forward_full(ist_ctx *ctx, const ist_params *params, const ist_batch *bt, float *logits, void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound) return fail(ctx, IST_ESTATE, "ist_forward_full: call ist_bind first");
+    ist_status cs = forward_full_checks(ctx, params, bt, logits, "ist_forward_full");
+    if (cs != IST_OK) return cs;
+    const int t = ctx->t, S = ctx->S;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = ctx->workspace;
+    // One group of full width: the activation regions hold S subnets of max_B x ldr each, which is
+    // exactly room for max_B rows of S * ldr >= N_l values.
+    FullFwdBuffers fb{};
+    for (int l = 1; l < t; ++l) {
+        const LayerPlan &L = ctx->layer[l - 1];
+        fb.act[l - 1] = ws + L.off_act; fb.z[l - 1] = ws + L.off_z; fb.zh[l - 1] = ws + L.off_zh;
+        fb.isg[l - 1] = ws + L.off_isg;
+        fb.pitch[l - 1] = (int64_t)S * L.ldr;
+    }
+    fb.partial = reinterpret_cast<float *>(ws + ctx->off_partial);
+    fb.partial_bytes = ctx->partial_bytes;
+    fb.zeros = ws + ctx->off_zeros;
+    ist_status rs = forward_full_run(ctx, params, bt, logits, fb, st);
+    if (rs != IST_OK) return rs;
     // Rows of full width overlay the subnets' padded rows: where a subnet row has padding columns
     // (R not a multiple of 8) they now hold values, and ist_subnet_steps relies on zeros there.
     bool padded = false;

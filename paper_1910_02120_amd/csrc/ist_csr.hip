@@ -9,6 +9,8 @@
 //             gradient).  The sum over b runs in ascending b so the result does not
 //             depend on scheduling: a bitmap (one bit per sample) per column is
 //             built with integer atomics, then one wavefront owns one column.
+#include <algorithm>
+
 #include "ist_internal.h"
 
 namespace ist {
@@ -49,10 +51,17 @@ __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
         p[i] = v;
 }
 
+hipError_t launch_fill_u32(void *p, int64_t n, uint32_t v, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<int64_t>(2048, (n + 255) / 256);
+    hipLaunchKernelGGL(k_fill_u32, dim3(blocks), dim3(256), 0, st, static_cast<uint32_t *>(p), n, v);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st)
 {
-    if (bytes / 4 > 0) hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, st, static_cast<uint32_t *>(p), (int64_t)(bytes / 4), 0u);
-    return hipGetLastError();
+    return launch_fill_u32(p, (int64_t)(bytes / 4), 0u, st);
 }
 
 // bitmap[g][col][b >> 5] |= 1 << (b & 31) for every non-zero (b, col) of group g

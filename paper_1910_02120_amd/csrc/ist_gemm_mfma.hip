@@ -907,6 +907,24 @@ template <> struct Cfg<BF16> { static constexpr int KG64 = 2, KG32 = 4, KT_SMALL
 // capped and every workgroup walks several tiles (prefetching across them); otherwise one
 // tile per workgroup.
 static thread_local const char *s_label = "";   // product and storage type of the launch in progress
+static thread_local double s_bytes = 0.0;        // its algorithmic HBM bytes
+
+// Bytes a product has to move when every operand element is read once and every result written once
+// (the update also reads the weights it rewrites; the ReLU mask of the backward-data product is read).
+static double algo_bytes(const GemmArgs &a, int epi, int esz)
+{
+    const double G = a.G, M = a.M, N = a.N, K = a.K, e = esz;
+    double b = G * (M * K + N * K) * e;
+    switch (epi) {
+    case EPI_FWD_RELU: b += G * M * N * e; break;
+    case EPI_FWD_LOGITS: case EPI_PARTIAL: b += G * M * N * 4.0; break;
+    case EPI_BWD_DATA: b += 2.0 * G * M * N * e; break;
+    case EPI_UPDATE: b += 2.0 * G * M * N * e; break;
+    case EPI_DZT: b += G * M * N * e; break;
+    default: break;   // EPI_LSE stores only the per-block statistics
+    }
+    return b;
+}
 
 template <int BM, int BN, typename K>
 static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, int splits, int kps, hipStream_t st,
@@ -919,7 +937,7 @@ static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, in
     char label[64];
     snprintf(label, sizeof(label), "gemm_%s_%dx%d_t%d%s%s", s_label, BM, BN, threads, persist ? "_persistent" : "",
              splits > 1 ? "_splitk" : "");
-    tag_kernel(label, 2.0 * a.M * a.N * (double)a.K * a.G, 0.0);
+    tag_kernel(label, 2.0 * a.M * a.N * (double)a.K * a.G, s_bytes);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty, stagger, stagger_sleeps);
 }
 
@@ -953,7 +971,7 @@ static SplitPlan plan_for(const GemmArgs &a, int epi, int esz)
     return p;
 }
 
-int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a)
+int gemm_splits(int dtype, int epi, const GemmArgs &a)
 {
     if (a.M <= 0 || a.N <= 0 || a.G <= 0) return 1;
     return plan_for(a, epi, dtype == IST_BF16 ? 2 : 4).splits;
@@ -968,6 +986,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
     static thread_local char lab[40];
     snprintf(lab, sizeof(lab), "%s_%s%s", kEpi[EPI], esz == 2 ? "bf16" : "f32", VEC ? "" : "_novec");
     s_label = lab;
+    s_bytes = algo_bytes(a, EPI, esz);
     const SplitPlan p = plan_for(a, EPI, esz);
     if (p.tile == 128) {
         constexpr int KTB = Cfg<D>::KT_BIG, STB = Cfg<D>::ST_BIG;
@@ -1102,7 +1121,7 @@ static bool update_shares_launch(const GemmArgs &a, int esz)
     return layout && vec && p.tile != 128 && total <= (1 << 20);
 }
 
-bool gemm_update_shares_launch_mfma(int dtype, const GemmArgs &a)
+bool gemm_update_shares_launch(int dtype, const GemmArgs &a)
 {
     return update_shares_launch(a, dtype == IST_BF16 ? 2 : 4);
 }
@@ -1113,7 +1132,7 @@ static hipError_t launch_updates_typed(const GemmArgs *args, int n, const BiasAr
 {
     const int esz = D::kBytes;
     GemmMulti mm{};
-    double flops = 0.0;
+    double flops = 0.0, bytes = 0.0;
     for (int i = 0; i < n; ++i) {
         const GemmArgs &a = args[i];
         if (a.M <= 0 || a.N <= 0 || a.G <= 0) continue;
@@ -1130,6 +1149,7 @@ static hipError_t launch_updates_typed(const GemmArgs *args, int n, const BiasAr
         mm.vecC[mm.n] = vec_c_ok(a, EPI_UPDATE, esz) ? 1 : 0;
         mm.first[mm.n + 1] = mm.first[mm.n] + (int)(total >= 4 * cap ? cap : total);
         flops += 2.0 * a.M * a.N * (double)a.K * a.G;
+        bytes += algo_bytes(a, EPI_UPDATE, esz);
         ++mm.n;
     }
     if (mm.n == 0) return hipGetLastError();
@@ -1152,13 +1172,13 @@ static hipError_t launch_updates_typed(const GemmArgs *args, int n, const BiasAr
     char label[64];
     snprintf(label, sizeof(label), "gemm_update_%s_64x64_t256_persistent_x%d%s", esz == 2 ? "bf16" : "f32", mm.n,
              mm.bias_blocks ? "_bias" : "");
-    tag_kernel(label, flops, 0.0);
+    tag_kernel(label, flops, bytes);
     hipLaunchKernelGGL((k_gemm_mfma_multi<D, false, false, EPI_UPDATE, 64, 64, 2, 2, 1, 3, true, 32>), dim3((unsigned)grid),
                        dim3(256), 0, st, mm);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
+hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
                                     hipStream_t st)
 {
     if (bias_done) *bias_done = false;
@@ -1168,7 +1188,7 @@ hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, cons
                              : launch_updates_typed<F32>(args, n, bias, bias_done, st);
 }
 
-hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st)
+hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)
 {
     if (a.M <= 0 || a.N <= 0 || a.G <= 0) return hipSuccess;
     if (a.zeros == nullptr) return hipErrorInvalidValue;

@@ -205,13 +205,9 @@ hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st);
 // launch only writes a.partial, laid out [g * splits + sp][M][N] in fp32 without the bias, and the
 // caller's next kernel adds the splits up; unsplit launches are not affected.
 int gemm_splits(int dtype, int epi, const GemmArgs &a);
-hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs &a, hipStream_t st);
-hipError_t launch_gemm_mfma(int dtype, int epi, const GemmArgs &a, hipStream_t st);
-int gemm_splits_mfma(int dtype, int epi, const GemmArgs &a);
 // The EPI_UPDATE products of several layers (independent of each other); small ones share one launch.
 // gemm_update_shares_launch tells which do (the others are better launched, and timed, one by one).
 bool gemm_update_shares_launch(int dtype, const GemmArgs &a);
-bool gemm_update_shares_launch_mfma(int dtype, const GemmArgs &a);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
@@ -248,8 +244,6 @@ bool bias_jobs_all_narrow(const BiasArgs &a, int dtype);
 // `bias` (optional): narrow bias updates of the same step; *bias_done = they were done inside the shared launch
 hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
                                hipStream_t st);
-hipError_t launch_gemm_updates_mfma(int dtype, const GemmArgs *args, int n, const BiasArgs *bias, bool *bias_done,
-                                    hipStream_t st);
 
 // sparse-input first layer (weights stored [G][N0][w])
 struct CsrArgs {
@@ -262,6 +256,8 @@ struct CsrArgs {
 // z_out != null: write the fp32 pre-activation there instead of ReLU(.) to h
 // zero fill by a kernel (safe to record into a HIP graph); bytes is rounded down to a multiple of 4
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st);
+// n 32-bit words set to v, by a kernel as well
+hipError_t launch_fill_u32(void *p, int64_t n, uint32_t v, hipStream_t st);
 // rowmajor: Wt is W_1 itself, [w][N0] (full-network evaluation), not the transposed subnet block
 hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out,
                               int dtype, hipStream_t st, bool rowmajor = false);

@@ -49,13 +49,7 @@ def test_steps_after_a_full_forward_still_match_oracle(name):
     ctx = P.context()
     ctx.partition(P.dW, P.db, P.dperm)
     ctx.forward_full(P.dW, P.db, cfg.B, X=P.dX, csr=P.dcsr)
-    loss = P.gpu_steps(ctx)
-    got = H.export_all(ctx, cfg)
-    subs = P.oracle_subnets()
-    want_loss = P.oracle_steps(subs)
-    tol = H.TOL[cfg.dtype]
-    H.compare_subnets(got, subs, cfg, tol)
-    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
+    H.check_training(P, ctx)
     ctx.close()
 
 

@@ -52,10 +52,21 @@ SHAPES = {
     # wide output layer with a full 256-row batch: the row-statistics pass takes its 256x256 blocks
     "wide-out-bf16-B256": _mk("wide-out-bf16-B256", "cfg5", dims=(200, 512, 33001), S=8, B=256, k=2,
                               nnz_per_row=10, lr=0.5),
-    # more layers than one bias launch, one bias-copy launch or one shared update launch takes (16 / 16 / 4)
-    "very-deep-f32": _mk("very-deep-f32", "cfg2", dims=(16,) + (32,) * 18 + (5,), S=2, B=6, k=2, lr=0.05),
+    # more layers than one bias launch, one bias-copy launch or one shared update launch takes (16 / 16 / 4);
+    # initial weights 1.5 x Xavier so that the gradient survives the 18 ReLU layers down to the first
+    "very-deep-f32": _mk("very-deep-f32", "cfg2", dims=(16,) + (32,) * 18 + (5,), S=2, B=6, k=2, lr=0.05,
+                         init_gain=1.5),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
+}
+
+
+# Tensors on which no check of the change over the steps can have power, per shape: their gradient is
+# (next to) zero by construction of the shape.
+WEAK = {
+    # one neuron per subnet and hidden layer: where that neuron's ReLU is off for the whole batch nothing below
+    # the output bias moves
+    "width-one-blocks-f32": ("W1", "b1", "W2", "b2", "W3"),
 }
 
 
@@ -103,13 +114,8 @@ def test_k_local_steps_match_oracle(name):
     P = H.Problem(cfg, has_bias="nobias" not in name, dev=_dev())
     ctx = P.context()
     ctx.partition(P.dW, P.db, P.dperm)
-    loss = P.gpu_steps(ctx)
-    got = H.export_all(ctx, cfg)
-    subs = P.oracle_subnets()
-    want_loss = P.oracle_steps(subs)
+    got, subs, loss, worst = H.check_training(P, ctx, weak=WEAK.get(name, ()))
     tol = H.TOL[cfg.dtype]
-    worst = H.compare_subnets(got, subs, cfg, tol)
-    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
     # and the merged full network: owned entries from the subnets, the rest untouched
     Wm = [w.clone() for w in P.dW]
     bm = [b.clone() for b in P.db] if P.has_bias else None
@@ -242,10 +248,7 @@ def test_batch_smaller_than_max_B(name):
     P = H.Problem(cfg, dev=_dev())
     big = ISTContext(cfg.dims, cfg.S, cfg.dtype, cfg.input, True, max_B=cfg.B + 19, device=_dev())
     big.partition(P.dW, P.db, P.dperm)
-    P.gpu_steps(big)
-    subs = P.oracle_subnets()
-    P.oracle_steps(subs)
-    H.compare_subnets(H.export_all(big, cfg), subs, cfg, H.TOL[cfg.dtype])
+    H.check_training(P, big, weak=WEAK.get(name, ()))
     big.close()
 
 
@@ -261,12 +264,7 @@ def test_smaller_batch_after_a_larger_one(name):
     ctx.partition(Pb.dW, Pb.db, Pb.dperm)
     Pb.gpu_steps(ctx)
     ctx.partition(Ps.dW, Ps.db, Ps.dperm)
-    loss = Ps.gpu_steps(ctx)
-    subs = Ps.oracle_subnets()
-    want_loss = Ps.oracle_steps(subs)
-    tol = H.TOL[cfg.dtype]
-    H.compare_subnets(H.export_all(ctx, small), subs, small, tol)
-    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
+    H.check_training(Ps, ctx, weak=WEAK.get(name, ()))
     ctx.close()
 
 
@@ -286,13 +284,8 @@ def test_csr_with_empty_rows_and_unused_columns():
     P.upload()
     ctx = P.context()
     ctx.partition(P.dW, P.db, P.dperm)
-    loss = P.gpu_steps(ctx)
-    subs = P.oracle_subnets()
-    before = [s[0][0].copy() for s in subs]
-    want_loss = P.oracle_steps(subs)
-    got = H.export_all(ctx, cfg)
-    H.compare_subnets(got, subs, cfg, H.TOL[cfg.dtype])
-    np.testing.assert_allclose(loss, want_loss, rtol=1e-2, atol=1e-4)
+    before = [s[0][0].copy() for s in P.oracle_subnets()]
+    got, subs, loss, _ = H.check_training(P, ctx)
     unused = np.arange(cfg.dims[0]) % 3 == 0
     for s in range(cfg.S):                           # bit-exact: nothing may touch those columns
         w0 = H.np_bits(before[s].astype(np.float32), cfg.dtype)
@@ -306,12 +299,18 @@ def test_single_class_and_as_many_subnets_as_neurons(dims, S, B):
     P = H.Problem(cfg, dev=_dev())
     ctx = P.context()
     ctx.partition(P.dW, P.db, P.dperm)
-    loss = P.gpu_steps(ctx)
-    subs = P.oracle_subnets()
-    want_loss = P.oracle_steps(subs)
-    H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, H.TOL[cfg.dtype])
-    np.testing.assert_allclose(loss, want_loss, rtol=1e-2, atol=1e-5)
+    # one class: the loss is constant, nothing has a gradient; one neuron per subnet and layer: where its
+    # ReLU is off for the whole batch nothing below the output bias moves
+    H.check_training(P, ctx, weak=("W1", "b1", "W2", "b2") if dims[-1] == 1 else ("W1", "b1", "W2", "b2", "W3"))
     ctx.close()
+
+
+# with the standardisation a hidden bias has no gradient at all (the mean is subtracted again)
+WEAK_NORM = {n: tuple(f"b{l}" for l in range(1, len(SHAPES[n].dims) - 1)) for n in
+             ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "big-tiles-bf16", "csr-f32", "cfg5-small",
+              "deep-bf16"]}
+# a batch of one sample standardises to zero everywhere: nothing below the output bias has a gradient
+WEAK_NORM["one-hidden-B1-f32"] = ("W1", "b1", "W2")
 
 
 @pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "big-tiles-bf16",
@@ -322,13 +321,8 @@ def test_k_local_steps_with_standardisation_match_oracle(name):
     P = H.Problem(cfg, dev=_dev(), normalize=True)
     ctx = P.context()
     ctx.partition(P.dW, P.db, P.dperm)
-    loss = P.gpu_steps(ctx)
-    subs = P.oracle_subnets()
-    want_loss = P.oracle_steps(subs)
-    tol = H.TOL[cfg.dtype]
-    worst = H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, tol)
-    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
-    print(f"{name} (standardised): worst parameter rel err {worst:.3e} (tol {tol})")
+    _, _, _, worst = H.check_training(P, ctx, weak=WEAK_NORM.get(name, ()))
+    print(f"{name} (standardised): worst parameter rel err {worst:.3e} (tol {H.TOL[cfg.dtype]})")
     ctx.close()
 
 
@@ -354,22 +348,19 @@ def test_k_local_steps_with_layer_factors_match_oracle(name, paper, normalize):
     P = H.Problem(cfg, dev=_dev(), normalize=normalize, scale=_factors(cfg, paper))
     ctx = P.context()
     ctx.partition(P.dW, P.db, P.dperm)
-    loss = P.gpu_steps(ctx)
-    subs = P.oracle_subnets()
-    want_loss = P.oracle_steps(subs)
-    tol = H.TOL[cfg.dtype]
-    worst = H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, tol)
-    np.testing.assert_allclose(loss, want_loss, rtol=5 * tol, atol=1e-4)
-    print(f"{name} (factors {P.scale}): worst parameter rel err {worst:.3e} (tol {tol})")
+    _, _, _, worst = H.check_training(P, ctx, weak=WEAK_NORM.get(name, ()) if normalize else WEAK.get(name, ()))
+    print(f"{name} (factors {P.scale}): worst parameter rel err {worst:.3e} (tol {H.TOL[cfg.dtype]})")
     ctx.close()
 
 
 @pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "cfg5-small",
                                   "csr-f32", "wide-out-f32", "deep-bf16", "width-one-blocks-f32", "cfg1-nobias-S1"])
 def test_resample_equals_merge_then_partition(name):
-    """ist_resample leaves the full network and the new subnets exactly as ist_merge followed by
-    ist_partition with the new permutation would (bit for bit), twice in a row (the two subnet
-    buffers change roles), and training continues identically afterwards."""
+    """ist_resample against the oracle: from the trained subnets as exported, the oracle's merge gives the
+    full network and the oracle's partition by the next permutation gives the new subnets; both must come
+    out of ist_resample bit for bit (Section 2.1: subnets are re-sampled after every J local iterations).
+    Twice in a row (the two subnet buffers change roles).  A second context doing ist_merge followed by
+    ist_partition must agree as well, and training continues identically afterwards."""
     cfg = SHAPES[name]
     has_bias = "nobias" not in name
     P = H.Problem(cfg, has_bias=has_bias, dev=_dev())
@@ -379,10 +370,15 @@ def test_resample_equals_merge_then_partition(name):
     bb = [x.clone() for x in P.db] if has_bias else None
     a.partition(Wa, ba, P.dperm)
     b.partition(Wb, bb, P.dperm)
+    full_W = [H.np_bits(w, cfg.dtype).copy() for w in P.Ws]               # the oracle's full network, raw bits
+    full_b = [x.astype(np.float32).copy() for x in P.bs] if has_bias else None
+    old_perms = P.perms
     for rnd in (1, 2):
         P.gpu_steps(a, loss=False)
         P.gpu_steps(b, loss=False)
-        perm = [torch.from_numpy(p).to(_dev()) for p in gen.make_perms(cfg, rnd)]
+        trained = H.export_all(a, cfg)
+        new_perms = gen.make_perms(cfg, rnd)
+        perm = [torch.from_numpy(p).to(_dev()) for p in new_perms]
         a.profile_enable(True)
         a.profile_reset()
         a.resample(Wa, ba, perm)
@@ -390,6 +386,28 @@ def test_resample_equals_merge_then_partition(name):
         a.profile_enable(False)
         if name in ("cfg1", "cfg3-small", "cfg4-small"):   # aligned shapes take the one-pass kernels
             assert {"k_resample_rows", "k_resample_mid"} <= labels, labels
+        # ---- the oracle's merge of the trained subnets, then its partition by the new permutation ----
+        typed = [([H.bits(w) for w in Wl], None) for Wl, _ in trained]
+        orc.merge(full_W, None, old_perms, cfg.S, typed)
+        if has_bias:
+            dummy = [np.zeros(w.shape, dtype=np.float32) for w in P.Ws]
+            f32subs = [([H.to_f32(w) for w in Wl], [H.to_f32(x) for x in bl]) for Wl, bl in trained]
+            orc.merge(dummy, full_b, old_perms, cfg.S, f32subs, mode=cfg.dtype)
+        raw_b = [H.np_bits(x, cfg.dtype) for x in full_b] if has_bias else [None] * cfg.t
+        want = orc.partition(full_W, raw_b, new_perms, cfg.S)
+        torch.cuda.synchronize()
+        for l in range(cfg.t):
+            assert np.array_equal(H.bits(Wa[l]), full_W[l]), (name, rnd, l, "merged weights vs oracle")
+            if has_bias:
+                assert np.array_equal(H.bits(ba[l]), raw_b[l]), (name, rnd, l, "merged bias vs oracle")
+        ga = H.export_all(a, cfg)
+        for s in range(cfg.S):
+            for l in range(cfg.t):
+                assert np.array_equal(H.bits(ga[s][0][l]), want[s][0][l]), (name, rnd, s, l, "new subnet weights vs oracle")
+                if has_bias:
+                    assert np.array_equal(H.bits(ga[s][1][l]), want[s][1][l]), (name, rnd, s, l, "new subnet bias vs oracle")
+        old_perms = new_perms
+        # ---- and the two separate calls ----
         b.merge(Wb, bb)
         b.partition(Wb, bb, perm)
         torch.cuda.synchronize()
@@ -397,7 +415,7 @@ def test_resample_equals_merge_then_partition(name):
             assert torch.equal(Wa[l], Wb[l]), (name, rnd, l, "merged weights")
             if has_bias:
                 assert torch.equal(ba[l], bb[l]), (name, rnd, l, "merged bias")
-        ga, gb = H.export_all(a, cfg), H.export_all(b, cfg)
+        gb = H.export_all(b, cfg)
         for s in range(cfg.S):
             for l in range(cfg.t):
                 assert torch.equal(ga[s][0][l], gb[s][0][l]), (name, rnd, s, l, "new subnet weights")
