@@ -179,6 +179,27 @@ ist_status ist_resample(ist_ctx *ctx, const ist_params *params, const int32_t *c
 ist_status ist_forward_full(ist_ctx *ctx, const ist_params *params, const ist_batch *batch,
                             float *logits /*[device]*/, void *stream);
 
+/*
+ * ist_forward_full_static - ist_forward_full for callers that cannot allocate device memory or hand
+ * over a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical logits, but it needs no ist_bind: the
+ * hidden activations, the standardisation's intermediates and the split-k partial sums live in a
+ * static device array of IST_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates nothing and frees nothing; it
+ * enqueues a clearing kernel for the part of the array it uses, then the pass itself.
+ *   - IST_ENOMEM (with a text in ist_last_error) if this network and batch need more than the array
+ *     holds: about B * sum of the hidden widths (rounded up to 8) * element size, plus B * width * 8
+ *     bytes per hidden layer with `normalize`, plus the split-k scratch of the context.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different
+ *     streams, or different contexts) race; callers serialise them.  It does not touch the bound
+ *     workspace, so it may overlap ist_subnet_steps.
+ *   - The first call on a device asks the runtime for the array's address; make that call once
+ *     before a stream capture begins.  Profiling brackets (ist_profile_enable) are not recorded.
+ */
+#define IST_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+ist_status ist_forward_full_static(ist_ctx *ctx, const ist_params *params, const ist_batch *batch,
+                                   float *logits /*[device]*/, void *stream);
+
 /* Canonical view of one subnet's layer l (1..t) for inspection and tests:
  * dstW [device] row-major [rows][cols] with rows/cols in the order of the
  * permutation block (H_l^s order), dstb [device] [rows] or NULL. */

@@ -26,7 +26,7 @@ EXPORTS = ["ist_create", "ist_destroy", "ist_subnets_bytes", "ist_workspace_byte
            "ist_subnet_shape", "ist_last_error", "ist_version", "ist_profile_enable",
            "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name",
            "ist_profile_kernel_count", "ist_profile_kernel", "ist_bind_spare", "ist_resample",
-           "ist_forward_full"]
+           "ist_forward_full", "ist_forward_full_static"]
 
 
 class ISTError(RuntimeError):
@@ -75,6 +75,7 @@ def load_library() -> C.CDLL:
     lib.ist_subnet_steps.argtypes = [p, C.POINTER(_Batch), C.c_float, C.c_int32, p, p]
     lib.ist_merge.argtypes = [p, C.POINTER(_Params), p]
     lib.ist_forward_full.argtypes = [p, C.POINTER(_Params), C.POINTER(_Batch), p, p]
+    lib.ist_forward_full_static.argtypes = [p, C.POINTER(_Params), C.POINTER(_Batch), p, p]
     lib.ist_bind_spare.argtypes = [p, p, C.c_size_t]
     lib.ist_resample.argtypes = [p, C.POINTER(_Params), C.POINTER(p), p]
     lib.ist_subnet_export.argtypes = [p, C.c_int32, C.c_int32, p, p, p]
@@ -227,9 +228,10 @@ class ISTContext:
         self._check(self.lib.ist_merge(self._ctx, C.byref(pr), _stream_ptr(stream)))
 
     def forward_full(self, Ws, bs, B: int, X: torch.Tensor = None, csr=None,
-                     logits: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                     logits: Optional[torch.Tensor] = None, stream=None, static: bool = False) -> torch.Tensor:
         """Logits [B][N_t] (float32) of the full network on samples 0..B-1 of X (rows of N_0
-        values) or of csr = (rowptr, colidx, vals)."""
+        values) or of csr = (rowptr, colidx, vals).  static: ist_forward_full_static (the library's own
+        scratch array instead of the bound workspace; `logits` must then be given: nothing is allocated)."""
         pr = self._params(Ws, bs)
         bt = _Batch()
         td = _torch_dtype(self.dtype)
@@ -245,11 +247,12 @@ class ISTContext:
             bt.x = X.data_ptr()
         bt.B = int(B)
         if logits is None:
+            assert not static, "ist_forward_full_static: pass the logits buffer"
             logits = torch.empty((B, self.dims[-1]), dtype=torch.float32, device=self.device)
         assert logits.is_cuda and logits.is_contiguous() and logits.dtype == torch.float32
         assert logits.numel() >= B * self.dims[-1]
-        self._check(self.lib.ist_forward_full(self._ctx, C.byref(pr), C.byref(bt), logits.data_ptr(),
-                                              _stream_ptr(stream)))
+        fn = self.lib.ist_forward_full_static if static else self.lib.ist_forward_full
+        self._check(fn(self._ctx, C.byref(pr), C.byref(bt), logits.data_ptr(), _stream_ptr(stream)))
         return logits
 
     def resample(self, Ws, bs, perms: List[torch.Tensor], stream=None):

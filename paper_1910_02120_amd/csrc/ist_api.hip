@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "ist_internal.h"
@@ -678,6 +679,87 @@ ist_status ist_forward_full(ist_ctx *ctx, const ist_params *params, const ist_ba
         IST_RUN(KC_BIAS_COPY, launch_fill_zero(ws + ctx->layer[0].off_act, ctx->off_zeros - ctx->layer[0].off_act, st),
                 "clear workspace");
     return IST_OK;
+}
+
+// ---- ist_forward_full_static: the same pass with its intermediate values in the library's own array ----
+// (the array lives in this file so that its address can be asked for here)
+constexpr size_t kStaticScratchBytes = IST_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device, asked for once per device (each GPU holds its
+// own copy of the array at its own address).  Host code must use this pointer: the array's name is
+// only a handle for hipGetSymbolAddress on the host side.
+static hipError_t static_scratch_ptr(char **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = static_cast<char *>(ptr[dev]);
+    return hipSuccess;
+}
+
+ist_status ist_forward_full_static(ist_ctx *ctx, const ist_params *params, const ist_batch *bt, float *logits,
+                                   void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    ist_status cs = forward_full_checks(ctx, params, bt, logits, "ist_forward_full_static");
+    if (cs != IST_OK) return cs;
+    const int t = ctx->t, e = ctx->esz();
+    const size_t B = (size_t)bt->B;
+    // layout inside the array, sized for this call's batch: zeros | per hidden layer h (and z, zh, 1/sigma) | split-K partials
+    FullFwdBuffers fb{};
+    size_t off = align_up(256);
+    size_t offs[64][4] = {};
+    for (int l = 1; l < t; ++l) {
+        const size_t pitch = (size_t)(ctx->layer[l - 1].N_out + 7) / 8 * 8;
+        fb.pitch[l - 1] = (int64_t)pitch;
+        offs[l - 1][0] = off; off = align_up(off + B * pitch * e);
+        if (ctx->normalize) {
+            offs[l - 1][1] = off; off = align_up(off + B * pitch * sizeof(float));
+            offs[l - 1][2] = off; off = align_up(off + B * pitch * e);
+            offs[l - 1][3] = off; off = align_up(off + pitch * sizeof(float));
+        }
+        if (off > kStaticScratchBytes) break;   // (also keeps the sums far from overflow)
+    }
+    const size_t off_partial = off;
+    off = align_up(off + ctx->partial_bytes);
+    if (off > kStaticScratchBytes) {
+        char msg[200];
+        snprintf(msg, sizeof(msg), "ist_forward_full_static: this network and batch need more than the %zu bytes of the "
+                                   "library's static scratch array; use ist_forward_full with a bound workspace",
+                 kStaticScratchBytes);
+        return fail(ctx, IST_ENOMEM, msg);
+    }
+    char *base = nullptr;
+    IST_HIP(static_scratch_ptr(&base), "ist_forward_full_static: address of the scratch array");
+    for (int l = 1; l < t; ++l) {
+        fb.act[l - 1] = base + offs[l - 1][0]; fb.z[l - 1] = base + offs[l - 1][1];
+        fb.zh[l - 1] = base + offs[l - 1][2]; fb.isg[l - 1] = base + offs[l - 1][3];
+    }
+    fb.partial = reinterpret_cast<float *>(base + off_partial);
+    fb.partial_bytes = ctx->partial_bytes;
+    fb.zeros = base;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The array keeps what the last call left: the zero block and the padding columns of the rows
+    // (read by 16-byte operand loads) must be zero again, so the part in use is cleared, by a kernel.
+    IST_HIP(launch_fill_zero(base, off_partial, st), "ist_forward_full_static: clear scratch");
+    const bool prof = ctx->prof_on;   // per-launch events would have to be created: not here
+    ctx->prof_on = false;
+    const ist_status rs = forward_full_run(ctx, params, bt, logits, fb, st);
+    ctx->prof_on = prof;
+    return rs;
 }
 
 ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t k, float *loss_out,
