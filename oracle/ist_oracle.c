@@ -23,7 +23,8 @@
  * Readings where the paper is silent (all restated in the design notes):
  *   ReLU hidden activations with ReLU'(0) = 0, mean softmax cross-entropy loss,
  *   hidden biases travel with their neuron, the shared output bias is replicated
- *   and averaged on merge, equal-size blocks of a uniform random permutation.
+ *   and averaged on merge, blocks of a uniform random permutation that are as
+ *   equal in size as the layer width allows.
  *
  * Arithmetic is fp64.  "mode" selects where values are rounded to a storage
  * type, emulating a device that keeps parameters, activations and activation
@@ -68,15 +69,21 @@ void ist_oracle_round_array(double *x, int64_t n, int32_t mode)
 
 /* ------------------------------------------------- blocks, partition, merge */
 
-/* Neurons of hidden layer l owned by subnet s: the s-th block of width N/S of
-   the layer's permutation, order kept (Section 2.1 "Constructing Subnets";
-   Appendix A: sum_s m^{(s)}_{l,i} = 1). Returns -1 if S does not divide N. */
-int32_t ist_oracle_block(const int32_t *perm, int64_t N, int32_t S, int32_t s, int32_t *out)
+/* Neurons of hidden layer l owned by subnet s: the s-th block of the layer's
+   permutation, order kept (Section 2.1 "Constructing Subnets": every hidden neuron is
+   assigned to exactly one of the n subnets; Appendix A: sum_s m^{(s)}_{l,i} = 1).  The
+   blocks are as equal as N allows: with N = q*S + r, the first r subnets own q + 1
+   neurons and the others q (equal blocks when S divides N), so subnet s starts at
+   position s*q + min(s, r).  Writes the block to out and returns its width, or -1 on
+   a bad argument. */
+int64_t ist_oracle_block(const int32_t *perm, int64_t N, int32_t S, int32_t s, int32_t *out)
 {
-    if (S <= 0 || N % S != 0 || s < 0 || s >= S) return -1;
-    int64_t w = N / S;
-    for (int64_t i = 0; i < w; ++i) out[i] = perm[(int64_t)s * w + i];
-    return 0;
+    if (S <= 0 || N < 0 || s < 0 || s >= S) return -1;
+    int64_t q = N / S, r = N % S;
+    int64_t start = (int64_t)s * q + (s < r ? s : r);
+    int64_t w = q + (s < r ? 1 : 0);
+    for (int64_t i = 0; i < w; ++i) out[i] = perm[start + i];
+    return w;
 }
 
 /* sub[i][j] = W[ridx[i]][cidx[j]] on raw elements of esz bytes; a NULL index

@@ -64,7 +64,7 @@ def _load():
     lib.ist_oracle_round.argtypes = [C.c_double, C.c_int32]
     lib.ist_oracle_round_array.restype = None
     lib.ist_oracle_round_array.argtypes = [p, C.c_int64, C.c_int32]
-    lib.ist_oracle_block.restype = C.c_int32
+    lib.ist_oracle_block.restype = C.c_int64
     lib.ist_oracle_block.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p]
     for fn in (lib.ist_oracle_gather, lib.ist_oracle_scatter):
         fn.restype = None
@@ -100,15 +100,17 @@ def round_store(x: float, mode: str) -> float:
 
 # ------------------------------------------------------------------ blocks
 def block(perm: np.ndarray, S: int, s: int) -> np.ndarray:
+    """H^s of one hidden layer: the s-th block of its permutation; when S does not divide the
+    width the first N mod S subnets own one neuron more."""
     perm = np.ascontiguousarray(perm, dtype=np.int32)
     N = perm.shape[0]
-    if S <= 0 or N % S:
-        raise ValueError("S must divide the layer width")
-    out = np.empty(N // S, dtype=np.int32)
-    rc = _load().ist_oracle_block(_ptr(perm), N, S, s, _ptr(out))
-    if rc:
+    if S <= 0 or not 0 <= s < S:
         raise ValueError("bad block request")
-    return out
+    out = np.empty(N // S + 1, dtype=np.int32)
+    w = _load().ist_oracle_block(_ptr(perm), N, S, s, _ptr(out))
+    if w < 0:
+        raise ValueError("bad block request")
+    return out[:w].copy()
 
 
 def blocks(perms: Sequence[np.ndarray], S: int) -> List[List[np.ndarray]]:

@@ -26,20 +26,32 @@ def _masks(perms, dims, S):
         else:
             pos = np.empty(dims[l], dtype=np.int64)
             pos[perms[l - 1]] = np.arange(dims[l])
-            w = dims[l] // S
-            m.append(np.stack([(pos // w == s).astype(np.int64) for s in range(S)]))
+            # owner of perm position p: blocks as equal as N allows, the first N mod S one wider
+            q, r = divmod(dims[l], S)
+            owner = np.where(pos < r * (q + 1), pos // (q + 1), r + (pos - r * (q + 1)) // max(q, 1))
+            m.append(np.stack([(owner == s).astype(np.int64) for s in range(S)]))
     return m
 
 
+RAGGED = [((6, 8, 13, 5), 3), ((5, 11, 9, 7, 3), 5), ((7, 17, 4), 7), ((4, 10, 10, 3), 4), ((3, 7, 5, 2), 5)]
+
+
 @pytest.mark.parametrize("dims,S", [((6, 8, 12, 5), 2), ((5, 12, 9, 6, 3), 3), ((7, 16, 4), 4),
-                                    ((3, 5, 7, 2), 1)])
+                                    ((3, 5, 7, 2), 1)] + RAGGED)
 def test_blocks_are_a_disjoint_cover(dims, S):
     cfg = _cfg(dims, S)
     perms = gen.make_perms(cfg)
     H = orc.blocks(perms, S)
     for l in range(1, cfg.t):
         allb = np.concatenate(H[l - 1])
-        assert all(len(h) == dims[l] // S for h in H[l - 1])
+        # sizes differ by at most one, the wider blocks first; equal when S divides N_l
+        sizes = [len(h) for h in H[l - 1]]
+        assert sum(sizes) == dims[l] and max(sizes) - min(sizes) <= 1 and sizes == sorted(sizes, reverse=True)
+        if dims[l] % S == 0:
+            assert all(n == dims[l] // S for n in sizes)
+        # the same split as a library routine makes of the permutation
+        for mine, ref in zip(H[l - 1], np.array_split(perms[l - 1], S)):
+            assert np.array_equal(mine, ref)
         assert np.array_equal(np.sort(allb), np.arange(dims[l]))   # each neuron exactly once
     m = _masks(perms, dims, S)
     for l in range(cfg.t + 1):
@@ -50,12 +62,20 @@ def test_blocks_are_a_disjoint_cover(dims, S):
                 assert np.array_equal(np.flatnonzero(m[l][s]), np.sort(H[l - 1][s]))
 
 
-def test_block_rejects_indivisible_width():
+def test_block_of_an_indivisible_width():
+    """10 neurons over 3 subnets: 4 + 3 + 3, in permutation order; out-of-range subnets are rejected."""
+    perm = np.array([7, 2, 9, 0, 4, 1, 8, 3, 6, 5], dtype=np.int32)
+    assert orc.block(perm, 3, 0).tolist() == [7, 2, 9, 0]
+    assert orc.block(perm, 3, 1).tolist() == [4, 1, 8]
+    assert orc.block(perm, 3, 2).tolist() == [3, 6, 5]
+    assert orc.block(perm, 10, 9).tolist() == [5]
     with pytest.raises(ValueError):
-        orc.block(np.arange(10, dtype=np.int32), 3, 0)
+        orc.block(perm, 3, 3)
+    with pytest.raises(ValueError):
+        orc.block(perm, 0, 0)
 
 
-@pytest.mark.parametrize("dims,S", [((6, 8, 12, 5), 2), ((5, 12, 9, 6, 3), 3), ((7, 16, 4), 4)])
+@pytest.mark.parametrize("dims,S", [((6, 8, 12, 5), 2), ((5, 12, 9, 6, 3), 3), ((7, 16, 4), 4)] + RAGGED)
 def test_partition_equals_masked_definition_and_numpy(dims, S):
     cfg = _cfg(dims, S)
     Ws, bs = gen.make_weights(cfg, bias_scale=0.3)
@@ -97,6 +117,52 @@ def test_parameter_counts_match_closed_form():
         p = d[0] * d[1] // S_ + sum(d[i - 1] * d[i] // S_ ** 2 for i in range(2, c.t)) \
             + d[c.t - 1] * d[c.t] // S_
         assert p == want[name]
+
+
+@pytest.mark.parametrize("dims,S", RAGGED)
+def test_parameter_counts_with_unequal_blocks(dims, S):
+    """With N_l = q_l S + r_l the subnets hold, over all s, N_0 N_1 + N_{t-1} N_t first- and last-layer
+    weights and, per middle matrix, sum_s w_l^s w_{l-1}^s = S q_l q_{l-1} + q_l r_{l-1} + q_{l-1} r_l +
+    min(r_l, r_{l-1}) weights (the wider blocks are the first ones in both layers)."""
+    cfg = _cfg(dims, S)
+    Ws, bs = gen.make_weights(cfg)
+    subs = orc.partition(Ws, bs, gen.make_perms(cfg), S)
+    t = cfg.t
+    for l in range(1, t + 1):
+        got = sum(subs[s][0][l - 1].size for s in range(S))
+        if l == 1 or l == t:
+            assert got == dims[l] * dims[l - 1]
+        else:
+            (q1, r1), (q0, r0) = divmod(dims[l], S), divmod(dims[l - 1], S)
+            assert got == S * q1 * q0 + q1 * r0 + q0 * r1 + min(r1, r0)
+        for s in range(S):
+            rows = dims[l] if l == t else dims[l] // S + (s < dims[l] % S)
+            cols = dims[l - 1] if l == 1 else dims[l - 1] // S + (s < dims[l - 1] % S)
+            assert subs[s][0][l - 1].shape == (rows, cols) and subs[s][1][l - 1].shape == (rows,)
+
+
+@pytest.mark.parametrize("dims,S", RAGGED)
+def test_round_trip_and_unowned_entries_with_unequal_blocks(dims, S):
+    cfg = _cfg(dims, S)
+    Ws, bs = gen.make_weights(cfg, bias_scale=0.2)
+    perms = gen.make_perms(cfg)
+    subs = orc.partition(Ws, bs, perms, S)
+    parts = [np.array_split(p, S) for p in perms]             # a library routine's split of the permutation
+    full = [np.full_like(w, 7.0) for w in Ws]
+    orc.merge(full, None, perms, S, subs)
+    for l in range(1, cfg.t + 1):
+        owned = np.zeros(Ws[l - 1].shape, bool)
+        for s in range(S):
+            rows = np.arange(dims[l]) if l == cfg.t else parts[l - 1][s]
+            cols = np.arange(dims[l - 1]) if l == 1 else parts[l - 2][s]
+            assert not owned[np.ix_(rows, cols)].any()        # no collisions
+            owned[np.ix_(rows, cols)] = True
+        assert np.array_equal(full[l - 1][owned], Ws[l - 1][owned]) and np.all(full[l - 1][~owned] == 7.0)
+    # hidden biases return to their neuron
+    fb = [np.full_like(b, 7.0) for b in bs]
+    orc.merge([w.copy() for w in Ws], fb, perms, S, subs)
+    for l in range(cfg.t - 1):
+        assert np.array_equal(fb[l], bs[l])
 
 
 def test_single_hidden_layer_owns_every_weight():

@@ -168,10 +168,11 @@ def test_S1_round_is_a_full_network_sgd_step():
         np.testing.assert_allclose(a, b, rtol=0, atol=1e-12)
 
 
-def test_subnet_equals_masked_full_network():
+@pytest.mark.parametrize("dims,S", [((6, 12, 8, 5), 4), ((6, 13, 7, 5), 4), ((5, 11, 9, 3), 3)])
+def test_subnet_equals_masked_full_network(dims, S):
     """Subnet loss = loss of the full network with every hidden neuron outside the
-    subnet zeroed (Appendix A without the n^2 factor)."""
-    cfg = _cfg((6, 12, 8, 5), S=4, B=9, k=1)
+    subnet zeroed (Appendix A without the n^2 factor); also with blocks of unequal width."""
+    cfg = _cfg(dims, S=S, B=9, k=1)
     Ws, bs = gen.make_weights(cfg, bias_scale=0.3)
     perms = gen.make_perms(cfg)
     X, y = gen.make_dense_batches(cfg)
@@ -179,12 +180,40 @@ def test_subnet_equals_masked_full_network():
     for s in range(cfg.S):
         masks = []
         for l in range(1, cfg.t):
-            pos = np.empty(cfg.dims[l], dtype=np.int64)
-            pos[perms[l - 1]] = np.arange(cfg.dims[l])
-            masks.append((pos // (cfg.dims[l] // cfg.S) == s).astype(np.float64))
+            # membership from the split of the permutation a library routine makes
+            m = np.zeros(cfg.dims[l])
+            m[np.array_split(perms[l - 1], cfg.S)[s]] = 1.0
+            masks.append(m)
         want, _ = _np_forward_loss(Ws, bs, X[s, 0], y[s, 0], masks)
         got = orc.subnet_sgd(*subs[s], y[s, :1], 0.0, 1, "exact", X=X[s, :1])[0]
         assert abs(got - want) < 1e-13
+
+
+@pytest.mark.parametrize("normalize", [False, True])
+@pytest.mark.parametrize("mode", ["exact", "f32", "bf16"])
+def test_a_neuron_with_zero_parameters_is_inert(mode, normalize):
+    """A hidden neuron whose incoming weights, bias and outgoing weights are all zero outputs ReLU(0) = 0,
+    receives no gradient and passes none on: training a subnet with such neurons appended to its hidden
+    layers leaves the real parameters exactly as training the subnet alone, and the added ones at zero.
+    (What a device may rely on to keep blocks of unequal width in arrays of one common size.)"""
+    cfg = _cfg((7, 5, 4, 6), S=1, B=8, k=4, dtype="bf16" if mode == "bf16" else "f32", lr=0.3)
+    Ws, bs = gen.make_weights(cfg, bias_scale=0.2)
+    X, y = gen.make_dense_batches(cfg)
+    Wa = [w.astype(np.float64) for w in Ws]
+    ba = [b.astype(np.float64) for b in bs]
+    pad = [0, 2, 1, 0]                                    # extra neurons per layer (hidden layers only)
+    Wb = [np.zeros((w.shape[0] + pad[l + 1], w.shape[1] + pad[l])) for l, w in enumerate(Wa)]
+    bb = [np.zeros(b.shape[0] + pad[l + 1]) for l, b in enumerate(ba)]
+    for l in range(cfg.t):
+        Wb[l][:Wa[l].shape[0], :Wa[l].shape[1]] = Wa[l]
+        bb[l][:ba[l].shape[0]] = ba[l]
+    la = orc.subnet_sgd(Wa, ba, y[0], cfg.lr, cfg.k, mode, X=X[0], normalize=normalize)
+    lb = orc.subnet_sgd(Wb, bb, y[0], cfg.lr, cfg.k, mode, X=X[0], normalize=normalize)
+    assert la.tobytes() == lb.tobytes()
+    for l in range(cfg.t):
+        r, c = Wa[l].shape
+        assert Wb[l][:r, :c].tobytes() == Wa[l].tobytes() and bb[l][:r].tobytes() == ba[l].tobytes()
+        assert not Wb[l][r:, :].any() and not Wb[l][:, c:].any() and not bb[l][r:].any()
 
 
 def test_one_hidden_layer_subnet_logits_sum_to_full_network():
