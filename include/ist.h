@@ -37,7 +37,7 @@ extern "C" {
 typedef enum {
     IST_OK = 0,
     IST_EINVAL = -1,       /* null pointer, non-positive size, bad enum */
-    IST_ESHAPE = -2,       /* S does not divide a hidden width, B > max_B, ... */
+    IST_ESHAPE = -2,       /* a hidden layer narrower than S, B > max_B, ... */
     IST_EPERM = -3,        /* a perm is not a permutation of 0..N_l-1 (checked mode) */
     IST_ENOMEM = -4,       /* a bound buffer is too small */
     IST_EHIP = -5,         /* a HIP runtime call failed */
@@ -51,7 +51,7 @@ typedef enum { IST_DENSE = 0, IST_CSR = 1 } ist_input_kind;
 /* The full network and how it is split. [host] */
 typedef struct {
     int32_t t;             /* number of weight matrices, >= 2 (at least one hidden layer) */
-    const int64_t *dims;   /* [host] N_0..N_t, t+1 entries; S must divide N_1..N_{t-1} */
+    const int64_t *dims;   /* [host] N_0..N_t, t+1 entries; every hidden width N_1..N_{t-1} >= S */
     int32_t S;             /* number of subnets, >= 1 */
     int32_t dtype;         /* ist_dtype: storage of W, b, activations, inputs */
     int32_t input;         /* ist_input_kind of the mini-batches */
@@ -94,7 +94,7 @@ typedef struct {
 typedef struct ist_ctx ist_ctx;
 
 /* Creates the host-side plan for one network shape.  No device work.
- * IST_ESHAPE if S does not divide a hidden width or max_B < 1; IST_EUNSUPPORTED if S > 4096. */
+ * IST_ESHAPE if a hidden layer has fewer than S neurons or max_B < 1; IST_EUNSUPPORTED if S > 4096. */
 ist_status ist_create(const ist_model_desc *desc, int32_t max_B, ist_ctx **out);
 ist_status ist_destroy(ist_ctx *ctx);
 
@@ -115,8 +115,10 @@ ist_status ist_set_checked(ist_ctx *ctx, int32_t checked);
 /*
  * ist_partition - Section 2.1 "Constructing Subnets", Appendix A.
  * perm[l-1] [device], l = 1..t-1, is a permutation of 0..N_l-1; subnet s owns
- * the neurons H_l^s = perm_l[s*N_l/S .. (s+1)*N_l/S - 1] of hidden layer l, and
- * all input and output neurons.  Copies W_l[H_l^s, H_{l-1}^s] and b_l[H_l^s]
+ * the s-th block H_l^s of perm_l, and all input and output neurons.  Blocks are as
+ * equal as the width allows: with N_l = q S + r the first r subnets own q + 1
+ * neurons and the others q, so H_l^s starts at position s q + min(s, r) (equal
+ * blocks perm_l[s*N_l/S .. (s+1)*N_l/S - 1] when S divides N_l).  Copies W_l[H_l^s, H_{l-1}^s] and b_l[H_l^s]
  * into the bound subnet buffer for every s (bit-exact copies; the output bias
  * b_t is replicated).  `params` is only read.
  */
@@ -206,8 +208,10 @@ ist_status ist_forward_full_static(ist_ctx *ctx, const ist_params *params, const
 ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, void *dstb,
                              void *stream);
 
-/* Rows and columns of subnet layer l as ist_subnet_export writes them. */
+/* Rows and columns of layer l of subnet s as ist_subnet_export writes them (ist_subnet_shape_of), and of
+ * the widest subnet, which is subnet 0 (ist_subnet_shape; every subnet's when S divides the hidden widths). */
 ist_status ist_subnet_shape(const ist_ctx *ctx, int32_t l, int64_t *rows, int64_t *cols);
+ist_status ist_subnet_shape_of(const ist_ctx *ctx, int32_t s, int32_t l, int64_t *rows, int64_t *cols);
 
 /*
  * Measurement support.  With profiling on, every kernel launch of the three hot

@@ -26,7 +26,7 @@ EXPORTS = ["ist_create", "ist_destroy", "ist_subnets_bytes", "ist_workspace_byte
            "ist_subnet_shape", "ist_last_error", "ist_version", "ist_profile_enable",
            "ist_profile_reset", "ist_profile_read", "ist_profile_classes", "ist_profile_class_name",
            "ist_profile_kernel_count", "ist_profile_kernel", "ist_bind_spare", "ist_resample",
-           "ist_forward_full", "ist_forward_full_static"]
+           "ist_forward_full", "ist_forward_full_static", "ist_subnet_shape_of"]
 
 
 class ISTError(RuntimeError):
@@ -80,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.ist_resample.argtypes = [p, C.POINTER(_Params), C.POINTER(p), p]
     lib.ist_subnet_export.argtypes = [p, C.c_int32, C.c_int32, p, p, p]
     lib.ist_subnet_shape.argtypes = [p, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.ist_subnet_shape_of.argtypes = [p, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.ist_profile_enable.argtypes = [p, C.c_int32]
     lib.ist_profile_reset.argtypes = [p]
     lib.ist_profile_read.argtypes = [p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -269,14 +270,18 @@ class ISTContext:
         self._check(self.lib.ist_resample(self._ctx, C.byref(pr), pp, _stream_ptr(stream)))
 
     # -- inspection ---------------------------------------------------------
-    def subnet_shape(self, l: int):
+    def subnet_shape(self, l: int, s: Optional[int] = None):
+        """(rows, cols) of layer l of subnet s; of the widest subnet when s is None."""
         r, c = C.c_int64(), C.c_int64()
-        self._check(self.lib.ist_subnet_shape(self._ctx, l, C.byref(r), C.byref(c)))
+        if s is None:
+            self._check(self.lib.ist_subnet_shape(self._ctx, l, C.byref(r), C.byref(c)))
+        else:
+            self._check(self.lib.ist_subnet_shape_of(self._ctx, s, l, C.byref(r), C.byref(c)))
         return r.value, c.value
 
     def subnet_export(self, s: int, l: int, stream=None):
         """(W_l^s [rows][cols], b_l^s [rows] or None) in permutation-block order."""
-        r, c = self.subnet_shape(l)
+        r, c = self.subnet_shape(l, s)
         td = _torch_dtype(self.dtype)
         W = torch.empty((r, c), dtype=td, device=self.device)
         b = torch.empty((r,), dtype=td, device=self.device) if self.has_bias else None

@@ -151,7 +151,7 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     if (d->S > 4096) return IST_EUNSUPPORTED;   // the output-bias mean is a two-level tree of 64
     for (int l = 0; l <= d->t; ++l) {
         if (d->dims[l] < 1 || d->dims[l] > 0x7fffffffLL) return IST_ESHAPE;
-        if (l > 0 && l < d->t && d->dims[l] % d->S != 0) return IST_ESHAPE;
+        if (l > 0 && l < d->t && d->dims[l] < d->S) return IST_ESHAPE;   // every subnet owns at least one neuron
     }
     ist_ctx *ctx = new (std::nothrow) ist_ctx();
     if (!ctx) return IST_ENOMEM;
@@ -169,8 +169,8 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     for (int l = 1; l < t; ++l) {
         HiddenPlan &h = ctx->hidden[l - 1];
         h.N = ctx->dims[l];
-        h.w = h.N / S;
-        h.off_sorted = off; off = align_up(off + sizeof(int32_t) * h.N);
+        h.w = (h.N + S - 1) / S;
+        h.off_sorted = off; off = align_up(off + sizeof(int32_t) * h.w * S);
         h.off_slot = off;   off = align_up(off + sizeof(int32_t) * h.N);
         h.off_p2q = off;    off = align_up(off + sizeof(int32_t) * h.N);
         h.words = (h.N + 31) / 32;
@@ -183,8 +183,8 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         LayerPlan &L = ctx->layer[l - 1];
         L.N_out = ctx->dims[l]; L.N_in = ctx->dims[l - 1];
         L.row_part = l < t; L.col_part = l > 1;
-        L.R = L.row_part ? L.N_out / S : L.N_out;
-        L.C = L.col_part ? L.N_in / S : L.N_in;
+        L.R = L.row_part ? ctx->hidden[l - 1].w : L.N_out;   // packed widths (the widest block's)
+        L.C = L.col_part ? ctx->hidden[l - 2].w : L.N_in;
         L.transposed = (l == 1 && d->input == IST_CSR);
         L.ldr = (L.R + 7) / 8 * 8;
         L.off_W = off; off = align_up(off + (size_t)S * L.R * L.C * e);
@@ -387,11 +387,25 @@ ist_status ist_set_checked(ist_ctx *ctx, int32_t checked)
     return IST_OK;
 }
 
+// rows / columns of layer l held by subnet s itself (blocks may differ by one neuron)
+static void own_shape(const ist_ctx *ctx, int32_t s, int32_t l, int64_t *rows, int64_t *cols)
+{
+    const LayerPlan &L = ctx->layer[l - 1];
+    *rows = L.row_part ? ctx->hidden[l - 1].width(s, ctx->S) : L.N_out;
+    *cols = L.col_part ? ctx->hidden[l - 2].width(s, ctx->S) : L.N_in;
+}
+
 ist_status ist_subnet_shape(const ist_ctx *ctx, int32_t l, int64_t *rows, int64_t *cols)
 {
     if (!ctx || !rows || !cols || l < 1 || l > ctx->t) return IST_EINVAL;
-    *rows = ctx->layer[l - 1].R;
-    *cols = ctx->layer[l - 1].C;
+    own_shape(ctx, 0, l, rows, cols);   // subnet 0 owns the widest blocks
+    return IST_OK;
+}
+
+ist_status ist_subnet_shape_of(const ist_ctx *ctx, int32_t s, int32_t l, int64_t *rows, int64_t *cols)
+{
+    if (!ctx || !rows || !cols || l < 1 || l > ctx->t || s < 0 || s >= ctx->S) return IST_EINVAL;
+    own_shape(ctx, s, l, rows, cols);
     return IST_OK;
 }
 
@@ -566,16 +580,20 @@ ist_status ist_subnet_export(ist_ctx *ctx, int32_t s, int32_t l, void *dstW, voi
     if (s < 0 || s >= ctx->S || l < 1 || l > ctx->t || !dstW) return fail(ctx, IST_EINVAL, "ist_subnet_export: bad argument");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const LayerPlan &L = ctx->layer[l - 1];
-    const int e = ctx->esz();
+    const int e = ctx->esz(), S = ctx->S;
     const int32_t *pr = L.row_part ? tbl(ctx->subnets, ctx->hidden[l - 1].off_p2q) : nullptr;
     const int32_t *pc = L.col_part ? tbl(ctx->subnets, ctx->hidden[l - 2].off_p2q) : nullptr;
+    int64_t nr, nc;
+    own_shape(ctx, s, l, &nr, &nc);
+    const int64_t perm_r = L.row_part ? ctx->hidden[l - 1].perm_start(s, S) : 0, pack_r = L.row_part ? (int64_t)s * L.R : 0;
+    const int64_t perm_c = L.col_part ? ctx->hidden[l - 2].perm_start(s, S) : 0, pack_c = L.col_part ? (int64_t)s * L.C : 0;
     const char *blk = ctx->subnets + L.off_W + (size_t)s * L.R * L.C * e;
-    IST_HIP(launch_export(blk, dstW, L.R, L.C, pr, (int64_t)s * L.R, pc, (int64_t)s * L.C, L.transposed, e, st),
+    IST_HIP(launch_export(blk, dstW, nr, nc, L.R, L.C, pr, perm_r, pack_r, pc, perm_c, pack_c, L.transposed, e, st),
             "export W");
     if (dstb) {
         if (!ctx->has_bias) return fail(ctx, IST_EINVAL, "ist_subnet_export: model has no bias");
         const char *bb = ctx->subnets + L.off_b + (size_t)s * L.R * e;
-        IST_HIP(launch_export(bb, dstb, L.R, 1, pr, (int64_t)s * L.R, nullptr, 0, false, e, st), "export b");
+        IST_HIP(launch_export(bb, dstb, nr, 1, L.R, 1, pr, perm_r, pack_r, nullptr, 0, 0, false, e, st), "export b");
     }
     return IST_OK;
 }

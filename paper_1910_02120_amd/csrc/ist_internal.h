@@ -61,8 +61,13 @@ struct LayerPlan {           // weight matrix l = 1..t
 };
 
 struct HiddenPlan {          // hidden layer l = 1..t-1
+    // N = q S + r neurons: the first r subnets own q + 1, the others q.  Every subnet's block is kept in
+    // w = ceil(N / S) packed positions; a position beyond the subnet's own width holds no neuron (its
+    // entry in `sorted` is -1, its weights and bias are zeros, which makes it inert in the local steps).
     int64_t N = 0, w = 0;
-    size_t off_sorted = 0;   // subnet buffer: int32 [N]  neuron id at sorted position P
+    int64_t width(int s, int S) const { return N / S + (s < N % S ? 1 : 0); }
+    int64_t perm_start(int s, int S) const { return (int64_t)s * (N / S) + (s < N % S ? s : N % S); }
+    size_t off_sorted = 0;   // subnet buffer: int32 [S * w]  neuron id at sorted position P = s * w + q, or -1
     size_t off_slot = 0;     // subnet buffer: int32 [N]  sorted position of neuron id
     size_t off_p2q = 0;      // subnet buffer: int32 [N]  sorted position of perm position p
     size_t off_mask = 0;     // subnet buffer: uint32 [S][words] bit c%32 of word c/32: neuron c is in subnet s
@@ -153,9 +158,12 @@ hipError_t launch_bias_replicate(const void *b, void *sub, int64_t n, int32_t G,
                                  hipStream_t st);
 hipError_t launch_bias_mean(void *b, const void *sub, int64_t n, int32_t G, int dtype,
                             hipStream_t st);
-hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc,
-                         const int32_t *p2q_r, int64_t base_r, const int32_t *p2q_c,
-                         int64_t base_c, bool transposed, int esz, hipStream_t st);
+// dst[i][j], i < nr, j < nc (the subnet's own widths, permutation order) from the packed block whose
+// rows / columns have pitch pr / pc positions; perm_r / pack_r: first permutation position and first
+// packed position of the subnet's row block (likewise for columns); null table = identity
+hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc, int64_t pr, int64_t pc,
+                         const int32_t *p2q_r, int64_t perm_r, int64_t pack_r, const int32_t *p2q_c,
+                         int64_t perm_c, int64_t pack_c, bool transposed, int esz, hipStream_t st);
 
 // ----------------------------------------------------------------- training
 enum Epilogue {

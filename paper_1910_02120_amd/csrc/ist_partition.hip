@@ -37,7 +37,7 @@ __global__ void k_perm_check(const int32_t *__restrict__ perm, const int32_t *__
 // the packed position of its first member without any dependence on other workgroups.
 constexpr int kSortThreads = 1024;
 __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
-    const int32_t *__restrict__ invpos, int64_t N, int64_t w, int32_t *__restrict__ sorted,
+    const int32_t *__restrict__ invpos, int64_t N, int64_t w, int32_t S, int32_t *__restrict__ sorted,
     int32_t *__restrict__ slot, int32_t *__restrict__ p2q, uint32_t *__restrict__ mask,
     int32_t *__restrict__ rank, int64_t words)
 {
@@ -46,7 +46,14 @@ __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
     const int s = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c0 = (int64_t)blockIdx.x * kSortThreads;
-    const int64_t p_lo = (int64_t)s * w, p_hi = p_lo + w;
+    // subnet s owns the permutation positions [p_lo, p_hi): N = q S + r, the first r blocks one wider;
+    // its packed positions are s * w + 0 .. w - 1 (w = ceil(N / S)), the last one empty in a narrower block
+    const int64_t qn = N / S, rn = N % S;
+    const int64_t ws = qn + (s < rn ? 1 : 0);
+    const int64_t p_lo = (int64_t)s * qn + (s < rn ? s : rn), p_hi = p_lo + ws;
+    const int64_t pack0 = (int64_t)s * w;
+    if (blockIdx.x == 0)
+        for (int64_t q = ws + threadIdx.x; q < w; q += kSortThreads) sorted[pack0 + q] = -1;
     int cnt = 0;
     for (int64_t c = threadIdx.x; c < c0; c += kSortThreads) {
         const int32_t p = invpos[c];
@@ -77,8 +84,8 @@ __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
     }
     if (mine) {
         const int64_t q = (int64_t)base + before + prefix;
-        if (q < w) {   // always true for a valid permutation
-            const int64_t P = p_lo + q;
+        if (q < ws) {   // always true for a valid permutation
+            const int64_t P = pack0 + q;
             sorted[P] = (int32_t)c;
             slot[c] = (int32_t)P;
             p2q[p] = (int32_t)P;
@@ -94,7 +101,7 @@ hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t
     const unsigned nb = (unsigned)((N + th - 1) / th);
     hipLaunchKernelGGL(k_perm_invert, dim3(nb), dim3(th), 0, st, perm, N, invpos, err);
     hipLaunchKernelGGL(k_perm_sort, dim3((unsigned)((N + kSortThreads - 1) / kSortThreads), (unsigned)S),
-                       dim3(kSortThreads), 0, st, invpos, N, N / S, sorted, slot, p2q, mask, rank, (N + 31) / 32);
+                       dim3(kSortThreads), 0, st, invpos, N, (N + S - 1) / S, S, sorted, slot, p2q, mask, rank, (N + 31) / 32);
     return hipGetLastError();
 }
 
@@ -117,8 +124,14 @@ __global__ __launch_bounds__(256) void k_rows(E *__restrict__ W, int64_t ld, E *
                                               int64_t nc)
 {
     for (int64_t P = blockIdx.x; P < nrows; P += gridDim.x) {
-        E *full = W + (int64_t)rows[P] * ld;
+        const int64_t r = rows[P];
         E *pack = sub + P * nc;
+        if (r < 0) {   // a packed position without a neuron (blocks of unequal width): zeros in, nothing out
+            if (!SCATTER)
+                for (int64_t i = threadIdx.x; i < nc; i += blockDim.x) pack[i] = E(0);
+            continue;
+        }
+        E *full = W + r * ld;
         if (VEC) {
             constexpr int per = 16 / sizeof(E);
             const int64_t nv = nc / per;
@@ -151,7 +164,10 @@ __global__ __launch_bounds__(256) void k_rows_transposed(E *__restrict__ W, int6
     if (!SCATTER) {
         for (int i = ty; i < 64; i += 4) {
             int64_t q = q0 + i, c = c0 + tx;
-            if (q < nr && c < nc) tile[i][tx] = W[(int64_t)rows[g * nr + q] * ld + c];
+            if (q < nr && c < nc) {
+                const int64_t r = rows[g * nr + q];   // -1: a packed position without a neuron
+                tile[i][tx] = r >= 0 ? W[r * ld + c] : E(0);
+            }
         }
         __syncthreads();
         for (int i = ty; i < 64; i += 4) {
@@ -166,7 +182,10 @@ __global__ __launch_bounds__(256) void k_rows_transposed(E *__restrict__ W, int6
         __syncthreads();
         for (int i = ty; i < 64; i += 4) {
             int64_t q = q0 + i, c = c0 + tx;
-            if (q < nr && c < nc) W[(int64_t)rows[g * nr + q] * ld + c] = tile[i][tx];
+            if (q < nr && c < nc) {
+                const int64_t r = rows[g * nr + q];
+                if (r >= 0) W[r * ld + c] = tile[i][tx];
+            }
         }
     }
 }
@@ -292,11 +311,16 @@ __global__ __launch_bounds__(256) void k_cols(E *__restrict__ W, int64_t ld, E *
     const int g = blockIdx.z;
     const int64_t i = blockIdx.y;
     const int64_t r = rows ? (int64_t)rows[g * nr + i] : i;
-    E *full = W + r * ld;
     E *pack = sub + ((int64_t)g * nr + i) * nc;
-    const int32_t *cg = cols + (int64_t)g * nc;
     constexpr int U = 4;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (r < 0) {   // a packed row without a neuron (blocks of unequal width): zeros in, nothing out
+        if (!SCATTER)
+            for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nc; q += stride) pack[q] = E(0);
+        return;
+    }
+    E *full = W + r * ld;
+    const int32_t *cg = cols + (int64_t)g * nc;
     for (int64_t q0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q0 < nc; q0 += stride * U) {
         int32_t c[U];
         E v[U];
@@ -308,12 +332,12 @@ __global__ __launch_bounds__(256) void k_cols(E *__restrict__ W, int64_t ld, E *
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t q = q0 + u * stride;
-            if (q < nc) v[u] = SCATTER ? pack[q] : full[c[u]];
+            if (q < nc) v[u] = SCATTER ? pack[q] : (c[u] >= 0 ? full[c[u]] : E(0));   // -1: a column without a neuron
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t q = q0 + u * stride;
-            if (q < nc) { if (SCATTER) full[c[u]] = v[u]; else pack[q] = v[u]; }
+            if (q < nc) { if (SCATTER) { if (c[u] >= 0) full[c[u]] = v[u]; } else pack[q] = v[u]; }
         }
     }
 }
@@ -471,8 +495,9 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
         const bool aligned = (reinterpret_cast<uintptr_t>(W) % 16 == 0) && (reinterpret_cast<uintptr_t>(sub) % 16 == 0) &&
                              (a.ld % EPC == 0) && (a.N_in % EPC == 0);
         const int64_t all_rows = a.nr * a.G;
+        // (blocks of equal width on both sides: no packed position without a neuron)
         if (a.slotr && aligned && a.rankc && a.N_in == a.ld && a.N_in % 32 == 0 && all_rows == a.N_out &&
-            all_rows < 0x7fffffffLL) {
+            a.nc * a.G == a.N_in && all_rows < 0x7fffffffLL) {
             tag_kernel(SCATTER ? "k_mid_lds<scatter>" : "k_mid_lds<gather>", 0.0, line_b);
             hipLaunchKernelGGL((k_mid_lds<E, SCATTER>), dim3((unsigned)all_rows), dim3(256), 0, st, W, a.ld, sub, a.slotr,
                                a.cols, a.rankc, a.wordsc, a.nr, a.nc, a.N_in, a.G);
@@ -630,7 +655,7 @@ static bool resample_typed(const CopyArgs &o, const CopyArgs &n, hipStream_t st)
     const int64_t all_rows = o.nr * o.G;
     if (o.rows) {    // middle layer
         if (!(o.slotr && n.slotr && o.rankc && n.rankc && o.N_in == o.ld && o.N_in % 32 == 0 && all_rows == o.N_out &&
-              all_rows < 0x7fffffffLL))
+              o.nc * o.G == o.N_in && all_rows < 0x7fffffffLL))
             return false;
         tag_kernel("k_resample_mid", 0.0, 2.0 * full_b + 2.0 * sub_b);
         hipLaunchKernelGGL((k_resample_mid<E>), dim3((unsigned)all_rows), dim3(256), 0, st, W, o.ld, so, sn, o.slotr, n.slotr,
@@ -705,7 +730,8 @@ __global__ void k_bias_rows(E *__restrict__ b, E *__restrict__ sub, const int32_
 {
     const int64_t P = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (P >= n) return;
-    if (SCATTER) b[rows[P]] = sub[P]; else sub[P] = b[rows[P]];
+    const int32_t r = rows[P];   // -1: a packed position without a neuron
+    if (SCATTER) { if (r >= 0) b[r] = sub[P]; } else sub[P] = r >= 0 ? b[r] : E(0);
 }
 
 hipError_t launch_bias_rows(void *b, void *sub, const int32_t *rows, int64_t n, int esz, bool scatter, hipStream_t st)
@@ -746,7 +772,8 @@ __global__ __launch_bounds__(256) void k_bias_jobs(BiasCopyJobs a)
     if (i >= jb.n) return;
     E *b = static_cast<E *>(jb.b), *sub = static_cast<E *>(jb.sub);
     if (jb.rows) {
-        if (SCATTER) b[jb.rows[i]] = sub[i]; else sub[i] = b[jb.rows[i]];
+        const int32_t r = jb.rows[i];   // -1: a packed position without a neuron
+        if (SCATTER) { if (r >= 0) b[r] = sub[i]; } else sub[i] = r >= 0 ? b[r] : E(0);
     } else if (!SCATTER) {
         const E v = b[i];
         for (int g = 0; g < jb.G; ++g) sub[(int64_t)g * jb.n + i] = v;
@@ -789,32 +816,32 @@ hipError_t launch_bias_mean(void *b, const void *sub, int64_t n, int32_t G, int 
 // export one subnet block in permutation order
 // ----------------------------------------------------------------------------
 template <typename E>
-__global__ void k_export(const E *__restrict__ sub, E *__restrict__ dst, int64_t nr, int64_t nc,
-                         const int32_t *__restrict__ p2q_r, int64_t base_r,
-                         const int32_t *__restrict__ p2q_c, int64_t base_c, bool transposed)
+__global__ void k_export(const E *__restrict__ sub, E *__restrict__ dst, int64_t nr, int64_t nc, int64_t pr, int64_t pc,
+                         const int32_t *__restrict__ p2q_r, int64_t perm_r, int64_t pack_r,
+                         const int32_t *__restrict__ p2q_c, int64_t perm_c, int64_t pack_c, bool transposed)
 {
     int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= nr * nc) return;
     int64_t i = idx / nc, j = idx % nc;
-    int64_t qi = p2q_r ? (int64_t)p2q_r[base_r + i] - base_r : i;
-    int64_t qj = p2q_c ? (int64_t)p2q_c[base_c + j] - base_c : j;
-    if (qi < 0 || qi >= nr || qj < 0 || qj >= nc) return;
-    dst[idx] = transposed ? sub[qj * nr + qi] : sub[qi * nc + qj];
+    int64_t qi = p2q_r ? (int64_t)p2q_r[perm_r + i] - pack_r : i;
+    int64_t qj = p2q_c ? (int64_t)p2q_c[perm_c + j] - pack_c : j;
+    if (qi < 0 || qi >= pr || qj < 0 || qj >= pc) return;
+    dst[idx] = transposed ? sub[qj * pr + qi] : sub[qi * pc + qj];
 }
 
-hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc, const int32_t *p2q_r,
-                         int64_t base_r, const int32_t *p2q_c, int64_t base_c, bool transposed,
-                         int esz, hipStream_t st)
+hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc, int64_t pr, int64_t pc,
+                         const int32_t *p2q_r, int64_t perm_r, int64_t pack_r, const int32_t *p2q_c,
+                         int64_t perm_c, int64_t pack_c, bool transposed, int esz, hipStream_t st)
 {
     int64_t n = nr * nc;
     if (n == 0) return hipSuccess;
     dim3 grid((unsigned)((n + 255) / 256));
     if (esz == 2)
-        hipLaunchKernelGGL(k_export<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)sub,
-                           (uint16_t *)dst, nr, nc, p2q_r, base_r, p2q_c, base_c, transposed);
+        hipLaunchKernelGGL(k_export<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)sub, (uint16_t *)dst, nr, nc, pr,
+                           pc, p2q_r, perm_r, pack_r, p2q_c, perm_c, pack_c, transposed);
     else
-        hipLaunchKernelGGL(k_export<uint32_t>, grid, dim3(256), 0, st, (const uint32_t *)sub,
-                           (uint32_t *)dst, nr, nc, p2q_r, base_r, p2q_c, base_c, transposed);
+        hipLaunchKernelGGL(k_export<uint32_t>, grid, dim3(256), 0, st, (const uint32_t *)sub, (uint32_t *)dst, nr, nc, pr,
+                           pc, p2q_r, perm_r, pack_r, p2q_c, perm_c, pack_c, transposed);
     return hipGetLastError();
 }
 

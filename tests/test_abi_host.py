@@ -57,7 +57,17 @@ def test_create_validates_the_description(lib):
     assert lib.ist_subnet_steps(ctx, None, C.c_float(0.1), 1, None, None) == -6
     assert b"partition" in lib.ist_last_error(ctx)
     assert lib.ist_destroy(ctx) == 0
-    assert _create(lib, [8, 10, 4], 4)[0] == -2          # S does not divide N_1
+    assert _create(lib, [8, 3, 4], 4)[0] == -2           # fewer hidden neurons than subnets
+    st, ctx = _create(lib, [8, 10, 7, 4], 4)             # blocks of unequal width: 10 = 3 + 3 + 2 + 2, 7 = 2 + 2 + 2 + 1
+    assert st == 0
+    got = []
+    for s_ in range(4):
+        assert lib.ist_subnet_shape_of(ctx, s_, 2, C.byref(r), C.byref(c)) == 0
+        got.append((r.value, c.value))
+    assert got == [(2, 3), (2, 3), (2, 2), (1, 2)]
+    assert lib.ist_subnet_shape(ctx, 2, C.byref(r), C.byref(c)) == 0 and (r.value, c.value) == (2, 3)
+    assert lib.ist_subnet_shape_of(ctx, 4, 2, C.byref(r), C.byref(c)) == -1
+    assert lib.ist_destroy(ctx) == 0
     assert _create(lib, [8, 16, 4], 0)[0] == -1          # S < 1
     assert _create(lib, [8, 4], 1)[0] == -1              # no hidden layer
     assert _create(lib, [8, 16, 4], 2, dtype=7)[0] == -1

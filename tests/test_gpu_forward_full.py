@@ -13,7 +13,8 @@ from test_gpu_parity import SHAPES
 pytestmark = pytest.mark.gpu
 
 CASES = ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "cfg5-small", "wide-out-f32",
-         "one-hidden-B1-f32", "deep-bf16", "width-one-blocks-f32", "csr-bf16-odd", "csr-f32", "mid-out-bf16"]
+         "one-hidden-B1-f32", "deep-bf16", "width-one-blocks-f32", "csr-bf16-odd", "csr-f32", "mid-out-bf16",
+         "uneven-S5-bf16", "uneven-S7-csr-bf16"]
 
 
 def _want(P, normalize):
@@ -42,7 +43,7 @@ def test_full_network_logits_match_oracle(name, normalize):
     ctx.close()
 
 
-@pytest.mark.parametrize("name", ["ragged-f32", "ragged-bf16", "csr-bf16-odd"])
+@pytest.mark.parametrize("name", ["ragged-f32", "ragged-bf16", "csr-bf16-odd", "uneven-S5-bf16"])
 def test_steps_after_a_full_forward_still_match_oracle(name):
     cfg = SHAPES[name]
     P = H.Problem(cfg, dev="cuda:0")

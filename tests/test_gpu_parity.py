@@ -58,6 +58,12 @@ SHAPES = {
                          init_gain=1.5),
     "csr-f32": _mk("csr-f32", "cfg5", dims=(517, 96, 301), S=4, B=33, k=3, nnz_per_row=9,
                    dtype="f32", lr=0.5),
+    # blocks of unequal width (S does not divide the hidden widths): 157 = 52 + 52 + 53 ..., a layer whose width
+    # S does divide next to one it does not, and the sparse first layer (stored transposed)
+    "uneven-S3-f32": _mk("uneven-S3-f32", "cfg2", dims=(100, 157, 203, 35), S=3, B=37, k=3, lr=0.05),
+    "uneven-S5-bf16": _mk("uneven-S5-bf16", "cfg3", dims=(150, 263, 320, 137, 10), S=5, B=45, k=3, lr=0.05),
+    "uneven-S7-csr-bf16": _mk("uneven-S7-csr-bf16", "cfg5", dims=(1000, 509, 77), S=7, B=21, k=2, nnz_per_row=12, lr=0.5),
+    "uneven-S7-wide-out-f32": _mk("uneven-S7-wide-out-f32", "cfg2", dims=(96, 131, 4507), S=7, B=24, k=2, lr=0.5),
 }
 
 
@@ -103,8 +109,17 @@ def test_partition_and_merge_are_bit_exact(name):
     for l in range(cfg.t):
         assert np.array_equal(H.bits(poison[l]), full[l]), (name, l)
     if P.has_bias:
+        # hidden biases return bit for bit; the output bias is the oracle's mean of the S copies (the copies
+        # themselves again when S is a power of two: every step of the pairwise sum and the scaling is exact)
+        fb = [b.astype(np.float32).copy() for b in P.bs]
+        f32subs = [([w for w in P.Ws], [H.to_f32(x) for x in bl]) for _, bl in got]
+        for s in range(cfg.S):
+            f32subs[s] = ([np.zeros(w.shape, dtype=np.float32) for w in want[s][0]], f32subs[s][1])
+        orc.merge([np.zeros(w.shape, dtype=np.float32) for w in P.Ws], fb, P.perms, cfg.S, f32subs, mode=cfg.dtype)
         for l in range(cfg.t):
-            assert np.array_equal(H.bits(pb[l]), raw_b[l]), (name, l, "bias round trip")
+            assert np.array_equal(H.bits(pb[l]), H.np_bits(fb[l], cfg.dtype)), (name, l, "bias round trip")
+            if l < cfg.t - 1 or cfg.S & (cfg.S - 1) == 0:
+                assert np.array_equal(H.bits(pb[l]), raw_b[l]), (name, l, "bias round trip, exact")
     ctx.close()
 
 
@@ -197,7 +212,7 @@ def test_error_paths():
         ctx.subnet_steps(P.dy, cfg.lr, 1, cfg.B + 1, X=P.dX)
     assert e.value.status == -2                       # B > max_B
     with pytest.raises(ISTError) as e:
-        ISTContext((8, 10, 4), 4, bind=False)
+        ISTContext((8, 3, 4), 4, bind=False)          # fewer hidden neurons than subnets
     assert e.value.status == -2
     ctx.close()
 
@@ -308,13 +323,14 @@ def test_single_class_and_as_many_subnets_as_neurons(dims, S, B):
 # with the standardisation a hidden bias has no gradient at all (the mean is subtracted again)
 WEAK_NORM = {n: tuple(f"b{l}" for l in range(1, len(SHAPES[n].dims) - 1)) for n in
              ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "big-tiles-bf16", "csr-f32", "cfg5-small",
-              "deep-bf16"]}
+              "deep-bf16", "uneven-S3-f32", "uneven-S5-bf16", "uneven-S7-csr-bf16"]}
 # a batch of one sample standardises to zero everywhere: nothing below the output bias has a gradient
 WEAK_NORM["one-hidden-B1-f32"] = ("W1", "b1", "W2")
 
 
 @pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "big-tiles-bf16",
-                                  "csr-f32", "cfg5-small", "one-hidden-B1-f32", "deep-bf16"])
+                                  "csr-f32", "cfg5-small", "one-hidden-B1-f32", "deep-bf16", "uneven-S3-f32",
+                                  "uneven-S5-bf16", "uneven-S7-csr-bf16"])
 def test_k_local_steps_with_standardisation_match_oracle(name):
     """Section 2.2: every hidden neuron's input standardised over the mini-batch before the ReLU."""
     cfg = SHAPES[name]
@@ -340,7 +356,8 @@ def _factors(cfg, paper):
     ("cfg3-small", False, False), ("cfg4-small", False, False), ("cfg5-small", False, False),
     ("csr-f32", False, False), ("wide-out-f32", False, False), ("many-steps-f32", False, False),
     ("mid-out-bf16", False, False), ("deep-bf16", False, False), ("speech-small", False, False),
-    ("cfg4-small", True, True), ("ragged-f32", False, True), ("cfg5-small", False, True)])
+    ("cfg4-small", True, True), ("ragged-f32", False, True), ("cfg5-small", False, True),
+    ("uneven-S5-bf16", True, False), ("uneven-S3-f32", False, False)])
 def test_k_local_steps_with_layer_factors_match_oracle(name, paper, normalize):
     """Appendix A, equation (4): the product of layer l multiplied by gamma_l in the forward pass, hence in
     both gradients.  With the standardisation the factor of a hidden layer only matters through epsilon."""
@@ -354,7 +371,8 @@ def test_k_local_steps_with_layer_factors_match_oracle(name, paper, normalize):
 
 
 @pytest.mark.parametrize("name", ["cfg1", "ragged-f32", "ragged-bf16", "cfg3-small", "cfg4-small", "cfg5-small",
-                                  "csr-f32", "wide-out-f32", "deep-bf16", "width-one-blocks-f32", "cfg1-nobias-S1"])
+                                  "csr-f32", "wide-out-f32", "deep-bf16", "width-one-blocks-f32", "cfg1-nobias-S1",
+                                  "uneven-S3-f32", "uneven-S5-bf16", "uneven-S7-csr-bf16"])
 def test_resample_equals_merge_then_partition(name):
     """ist_resample against the oracle: from the trained subnets as exported, the oracle's merge gives the
     full network and the oracle's partition by the next permutation gives the new subnets; both must come
