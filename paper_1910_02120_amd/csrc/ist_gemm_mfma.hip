@@ -403,6 +403,31 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
     f32x16 acc[TM][TN];
     typename TA::Regs ra[ST];
     typename TB::Regs rb[ST];
+    // Epilogue geometry: a lane finishes 8 consecutive columns of one row; CPR such chunks per row of the wave
+    // tile, RPP rows per pass of the wave, NP passes per 32-row slice.
+    constexpr int CPR = 32 * TN / 8;
+    constexpr int RPP = 64 / CPR;
+    constexpr int NP = 32 / RPP;
+    using T = typename D::T;
+    constexpr bool PRE = (EPI == EPI_UPDATE || EPI == EPI_BWD_DATA);
+    constexpr int PD = !PRE ? 1 : (DB ? TM : ((D::kBytes == 2 && !PERSIST) ? 2 : 1));
+    // Old weights (update) / activations (ReLU mask) of the chunks this lane will finish in row slice i of the
+    // tile at (tg, tm0, tn0), as raw 16-byte pieces.
+    auto preload = [&](int i, Pre8<T> (&dst)[NP], int tg, int tm0, int tn0) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int m = tm0 + wm + i * 32 + p * RPP + lane / CPR;
+            const int n = tn0 + wn + 8 * (lane % CPR);
+            const bool ok = vecC && kg == 0 && m < a.M && n + 8 <= a.N;
+            const T *src = EPI == EPI_UPDATE
+                               ? static_cast<const T *>(a.C) + (int64_t)tg * a.gC + (int64_t)m * a.ldc + n
+                               : static_cast<const T *>(a.mask) + (int64_t)tg * a.gMask + (int64_t)m * a.ldm + n;
+            const uint4 *q = reinterpret_cast<const uint4 *>(ok ? src : reinterpret_cast<const T *>(Z));
+#pragma unroll
+            for (int w = 0; w < (int)(sizeof(T) / 2); ++w) dst[p].v[w] = ok ? q[w] : uint4{0, 0, 0, 0};
+        }
+    };
+    Pre8<T> pre[PD][NP];
     auto prologue = [&]() {
 #pragma unroll
         for (int s = 0; s < ST; ++s) {
@@ -628,8 +653,6 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
         } else {
         // ---- epilogue through LDS: each lane gets 8 consecutive columns of one row ----
         float *stage = fsm + w4 * (32 * LDC);
-        constexpr int CPR = 32 * TN / 8;   // 8-column chunks per row of the wave tile
-        constexpr int RPP = 64 / CPR;      // rows per pass
         // per-row inputs of the cross-entropy epilogues, fetched in one batch up front
         // the 8 columns a lane finishes are the same in every row slice: one bias fetch per tile
         float bias8[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
@@ -662,32 +685,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
                                      ? D::ld(static_cast<const typename D::T *>(a.bias) + (int64_t)cg * a.gBias + m) : 0.0f;
                 }
         }
-        // Old weights (update) / activations (ReLU mask) of the chunks this lane will finish,
-        // PD row slices ahead: the loads are independent of the stores of earlier chunks, which
-        // the compiler cannot know, and would otherwise each wait out a full memory round trip.
-        using T = typename D::T;
-        constexpr bool PRE = (EPI == EPI_UPDATE || EPI == EPI_BWD_DATA);
-        constexpr int NP = 32 / RPP;
-        constexpr int PD = !PRE ? 1 : (DB ? TM : ((D::kBytes == 2 && !PERSIST) ? 2 : 1));
-        Pre8<T> pre[PD][NP];
-        auto preload = [&](int i, Pre8<T> (&dst)[NP]) {
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                const int m = cm0 + wm + i * 32 + p * RPP + lane / CPR;
-                const int n = cn0 + wn + 8 * (lane % CPR);
-                const bool ok = vecC && kg == 0 && m < a.M && n + 8 <= a.N;
-                const T *src = EPI == EPI_UPDATE
-                                   ? static_cast<const T *>(a.C) + (int64_t)cg * a.gC + (int64_t)m * a.ldc + n
-                                   : static_cast<const T *>(a.mask) + (int64_t)cg * a.gMask + (int64_t)m * a.ldm + n;
-                const uint4 *q = reinterpret_cast<const uint4 *>(ok ? src : reinterpret_cast<const T *>(Z));
-#pragma unroll
-                for (int w = 0; w < (int)(sizeof(T) / 2); ++w) dst[p].v[w] = ok ? q[w] : uint4{0, 0, 0, 0};
-            }
-        };
+        // The old weights / activations are fetched PD row slices ahead: the loads are independent of the
+        // stores of earlier chunks, which the compiler cannot know, and would otherwise each wait out a full
+        // memory round trip.
         if (PRE) {
 #pragma unroll
             for (int d = 0; d < PD; ++d)
-                if (d < TM) preload(d, pre[d]);
+                if (d < TM) preload(d, pre[d], cg, cm0, cn0);
         }
         // The MFMAs take the operands swapped, i.e. they produce the transposed 32x32 blocks:
         // accumulator v of block (i, j) is row 32 i + lane % 32, column 32 j + 8 (v / 4) +
@@ -731,7 +735,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
                                           val, vecC, bias8, pre[i % PD][p]);
                 }
             }
-            if (PRE && i + PD < TM) preload(i + PD, pre[i % PD]);
+            if (PRE && i + PD < TM) preload(i + PD, pre[i % PD], cg, cm0, cn0);
         }
         }
         if (!more) break;
@@ -753,8 +757,8 @@ __global__ IST_GEMM_BOUNDS
 void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x, int tiles_y, int stagger,
                  int stagger_sleeps)
 {
-    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB, false>(a, vecC, splits, k_per_split, tiles_x,
-                                                                                     tiles_y, stagger, stagger_sleeps, 0, 0);
+    gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB, false>(
+        a, vecC, splits, k_per_split, tiles_x, tiles_y, stagger, stagger_sleeps, 0, 0);
 }
 
 // Several independent products of one shape class in one launch (the weight updates of all layers of a

@@ -9,6 +9,15 @@
 
 namespace ist {
 
+// 16-byte load of data that is read exactly once (a row of the full matrix on its way into the
+// subnets): non-temporal, measured 6.3 .. 6.9 TB/s against 5.7 .. 6.2 TB/s for plain loads
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 ld_stream(const uint4 *p)
+{
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return uint4{v.x, v.y, v.z, v.w};
+}
+
 // ----------------------------------------------------------------------------
 // index tables
 // ----------------------------------------------------------------------------
@@ -138,7 +147,7 @@ __global__ __launch_bounds__(256) void k_rows(E *__restrict__ W, int64_t ld, E *
             uint4 *f4 = reinterpret_cast<uint4 *>(full);
             uint4 *p4 = reinterpret_cast<uint4 *>(pack);
             for (int64_t i = threadIdx.x; i < nv; i += blockDim.x) {
-                if (SCATTER) f4[i] = p4[i]; else p4[i] = f4[i];
+                if (SCATTER) f4[i] = p4[i]; else p4[i] = ld_stream(f4 + i);
             }
         } else {
             for (int64_t i = threadIdx.x; i < nc; i += blockDim.x) {
@@ -372,7 +381,7 @@ __global__ __launch_bounds__(256) void k_mid_lds(E *__restrict__ W, int64_t ld, 
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
         const int64_t c = threadIdx.x + 256 * u;
-        nxt[u] = c < row_pieces ? full[c] : uint4{0, 0, 0, 0};
+        nxt[u] = c < row_pieces ? (SCATTER ? full[c] : ld_stream(full + c)) : uint4{0, 0, 0, 0};
     }
     for (int64_t c0 = 0; c0 < N_in; c0 += kMidChunk) {
         const int64_t cend = c0 + kMidChunk < N_in ? c0 + kMidChunk : N_in;
@@ -387,7 +396,7 @@ __global__ __launch_bounds__(256) void k_mid_lds(E *__restrict__ W, int64_t ld, 
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int64_t c = (c0 + kMidChunk) / EPC + threadIdx.x + 256 * u;
-            nxt[u] = c < row_pieces ? full[c] : uint4{0, 0, 0, 0};
+            nxt[u] = c < row_pieces ? (SCATTER ? full[c] : ld_stream(full + c)) : uint4{0, 0, 0, 0};
         }
         for (int64_t q = qlo + threadIdx.x; q < qhi; q += 256) {
             const int64_t off = (int64_t)cg[q] - c0;
@@ -425,7 +434,7 @@ __global__ __launch_bounds__(256) void k_last_lds(E *__restrict__ W, int64_t ld,
     const int64_t nunit = (int64_t)G * nc / EPC;
     if (!SCATTER) {
         for (int64_t c = threadIdx.x; c < nchunk; c += blockDim.x)
-            reinterpret_cast<uint4 *>(row)[c] = full[c];
+            reinterpret_cast<uint4 *>(row)[c] = ld_stream(full + c);
         __syncthreads();
         for (int64_t u = threadIdx.x; u < nunit; u += blockDim.x) {
             const int64_t P0 = u * EPC;
