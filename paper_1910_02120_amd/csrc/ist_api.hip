@@ -197,6 +197,10 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     // Output layers wider than 4096 classes use the two-pass cross-entropy that recomputes the
     // logits instead of storing them (B x N_t fp32 per subnet would dominate HBM traffic).
     ctx->fused_out = ctx->dims[t] > 4096;
+    // a wide bf16 output layer behind a narrow hidden layer takes the two fused persistent launches of
+    // ist_wideout.hip: dz_t then only ever exists tile by tile in LDS
+    ctx->wide_out = ctx->fused_out && !ctx->layer[t - 1].transposed &&
+                    wide_out_supported(ctx->dtype, max_B, ctx->layer[t - 1].C, ctx->dims[t]);
     size_t w = 0;
     for (int l = 1; l < t; ++l) {
         ctx->hidden[l - 1].off_invpos = w;
@@ -208,7 +212,8 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         if (l == t && ctx->fused_out) act_e = 0;   // logits of a wide output layer are never stored
         L.off_act = w; w = align_up(w + (size_t)S * max_B * L.ldr * act_e);
         // the dz of a wide output layer is kept transposed, [S][N_t][max_B rounded up to 8]
-        const size_t dz_elems = (l == t && ctx->fused_out) ? (size_t)S * L.R * ((max_B + 7) / 8 * 8) : (size_t)S * max_B * L.ldr;
+        const size_t dz_elems = (l == t && ctx->wide_out) ? 0
+                              : (l == t && ctx->fused_out) ? (size_t)S * L.R * ((max_B + 7) / 8 * 8) : (size_t)S * max_B * L.ldr;
         L.off_dz = w;  w = align_up(w + dz_elems * e);
         if (ctx->normalize && l < t) {
             L.off_z = w;   w = align_up(w + (size_t)S * max_B * L.ldr * sizeof(float));
@@ -226,7 +231,7 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
         ctx->off_zlabel = w; w = align_up(w + sizeof(float) * rows);
         ctx->off_lse = w; w = align_up(w + sizeof(float) * rows);
         // bias gradient of the output layer as partial sums per class and block of >= 32 samples
-        if (ctx->has_bias)
+        if (ctx->has_bias && !ctx->wide_out)
             { ctx->off_rsum = w; w = align_up(w + sizeof(float) * (size_t)S * ((max_B + 31) / 32) * ctx->dims[t]); }
     }
     ctx->off_zeros = w; w = align_up(w + 256);   // stays zero: source of out-of-range operand chunks
@@ -246,6 +251,11 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
             SplitPlan b = plan_gemm(max_B, (int32_t)L.C, (int32_t)L.R, S, true, e);
             if (b.splits > 1) pmax = std::max(pmax, (size_t)S * b.splits * max_B * L.C * sizeof(float));
         }
+    }
+    // the workgroups of the fused wide-output launches leave their shares of dh in the same scratch
+    if (ctx->wide_out) {
+        ctx->wide_nb = wide_out_workgroups(S);
+        pmax = std::max(pmax, (size_t)S * ctx->wide_nb * max_B * ctx->layer[t - 1].C * sizeof(float));
     }
     ctx->off_partial = w; ctx->partial_bytes = pmax; w = align_up(w + pmax);
     ctx->workspace_bytes = w;
@@ -810,6 +820,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
         const int64_t row0 = (int64_t)j * bt->stride_k;
         float *rowloss = rowloss0 + (size_t)(j % kLossSlots) * S * B;
         int out_splits = 1, out_nrb = 0;
+        WideOutArgs wide{};
         // ---------------- forward ----------------
         for (int l = 1; l <= t; ++l) {
             const LayerPlan &L = ctx->layer[l - 1];
@@ -841,6 +852,29 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
             a.M = B; a.N = (int32_t)L.R; a.K = (int32_t)L.C; a.G = S;
             a.bias = bias; a.gBias = L.R;
             a.alpha = ctx->scale[l - 1];
+            if (l == t && ctx->wide_out) {
+                // statistics launch, merge into log-sum-exp and loss; the backward launch follows below
+                WideOutArgs wa{};
+                wa.h = a.A; wa.ldh = a.sam; wa.gH = a.gA;
+                wa.W = sb + L.off_W; wa.gW = L.R * L.C;
+                wa.bias = ctx->has_bias ? sb + L.off_b : nullptr; wa.gBias = L.R;
+                wa.y = bt->y + row0; wa.gY = bt->stride_s;
+                wa.G = S; wa.B = B; wa.C = (int32_t)L.C; wa.N = L.R;
+                wa.alpha = ctx->scale[t - 1]; wa.lr_w = lr * ctx->scale[t - 1]; wa.lr_b = lr; wa.invB = 1.0f / (float)B;
+                wa.pmax = reinterpret_cast<float *>(ws + ctx->off_pmax);
+                wa.psum = reinterpret_cast<float *>(ws + ctx->off_psum);
+                wa.nb = ctx->wide_nb;
+                wa.zlabel = reinterpret_cast<float *>(ws + ctx->off_zlabel);
+                wa.lse = reinterpret_cast<float *>(ws + ctx->off_lse);
+                wa.partial = reinterpret_cast<float *>(ws + ctx->off_partial);
+                IST_RUN(KC_GEMM_FWD, launch_wide_out_stats(wa, st), "wide output layer: row statistics");
+                IST_RUN(KC_SOFTMAX_XENT, launch_lse_combine(wa.pmax, wa.psum, wa.nb, reinterpret_cast<float *>(ws + ctx->off_qmax),
+                                                           reinterpret_cast<float *>(ws + ctx->off_qsum), wa.zlabel, wa.y, wa.gY, L.R,
+                                                           reinterpret_cast<float *>(ws + ctx->off_lse), rowloss, S, B, st),
+                        "combine row statistics");
+                wide = wa;
+                continue;
+            }
             if (l == t && ctx->fused_out) {
                 // pass 1: per-row, per-column-block max / sum(exp); pass 2 (after the row
                 // statistics are combined): recompute the logits and store dz_t directly
@@ -920,6 +954,25 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
         // ---------------- backward + update, top layer first ----------------
         for (int l = t; l >= 1; --l) {
             const LayerPlan &L = ctx->layer[l - 1];
+            if (l == t && ctx->wide_out) {
+                // dz_t, the update of W_t and b_t and the workgroups' shares of dh in one launch; then their sum,
+                // masked by h_{t-1} > 0, is dz_{t-1}
+                const LayerPlan &P = ctx->layer[l - 2];
+                IST_RUN(KC_GEMM_UPDATE, launch_wide_out_backward(wide, st), "wide output layer: backward and update");
+                GemmArgs a{};
+                set_split(ctx, a);
+                a.C = ws + P.off_dz; a.ldc = P.ldr; a.gC = (int64_t)B * P.ldr;
+                a.M = B; a.N = (int32_t)L.C; a.K = (int32_t)L.R; a.G = S;
+                a.mask = ws + P.off_act; a.ldm = P.ldr; a.gMask = (int64_t)B * P.ldr;
+                a.alpha = ctx->scale[l - 1];
+                IST_RUN(KC_GEMM_BWD_DATA, launch_splitk_finish_bwd(dt, a, wide.partial, wide.nb, st),
+                        "wide output layer: sum of the dh shares");
+                if (ctx->normalize)
+                    IST_RUN(KC_NORM, launch_norm_backward(ws + P.off_dz, ws + P.off_zh,
+                                        reinterpret_cast<const float *>(ws + P.off_isg), S, B, P.R, P.ldr, dt, st),
+                            "standardise (backward)");
+                continue;
+            }
             if (l > 1) {   // dz_{l-1} = (dz_l W_l) masked by h_{l-1} > 0, old W_l
                 const LayerPlan &P = ctx->layer[l - 2];
                 GemmArgs a{};
@@ -990,6 +1043,7 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
                 ba.B = B; ba.G = S; ba.lr = lr;
                 for (int l = l0; l <= t && l < l0 + kMaxBiasJobs; ++l) {
                     const LayerPlan &L = ctx->layer[l - 1];
+                    if (l == t && ctx->wide_out) continue;   // updated by the backward launch
                     if (l == t && ctx->fused_out) {
                         IST_RUN(KC_BIAS_UPDATE, launch_bias_apply(sb + L.off_b, reinterpret_cast<const float *>(ws + ctx->off_rsum),
                                                                   out_nrb, L.R, S, lr, dt, st),

@@ -30,15 +30,12 @@
 // The update products of several small layers, and their bias updates, can share one launch.
 #include "ist_internal.h"
 #include "ist_bias_block.h"
+#include "ist_mfma.h"
 
 #include <cstdio>
 
 namespace ist {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 template <typename D, int KT> struct Mma;   // KT: k extent of one LDS tile
 
@@ -51,33 +48,13 @@ template <int KT> struct Mma<BF16, KT> {
     // [k][row] row pitch: +32 elements (16 words) keeps the four k-rows one transposing
     // read touches in distinct bank groups (measured: SQ_LDS_BANK_CONFLICT drops ~10x vs +16)
     static constexpr int ld_m(int rows) { return rows + 32; }
-    __device__ static inline f32x16 mma(Frag a, Frag b, f32x16 c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-    }
+    __device__ static inline f32x16 mma(Frag a, Frag b, f32x16 c) { return bf16_mma(a, b, c); }
     __device__ static inline void store_k(E *lds, int row, int kc, uint4 v, int ld)
     {
         *reinterpret_cast<uint4 *>(lds + row * ld + kc * CH) = v;
     }
-    __device__ static inline Frag frag_k(const E *lds, int rb, int ks, int lane, int ld)
-    {
-        return *reinterpret_cast<const Frag *>(lds + (rb + (lane & 31)) * ld + ks * 16 + (lane >> 5) * 8);
-    }
-    __device__ static inline Frag frag_m(const E *lds, int rb, int ks, int lane, int ld)
-    {
-        // 16-lane block: lane q supplies the address of 4 consecutive row-elements
-        // [k0 + q/4][m0 + 4*(q%4)] and receives [k0 .. k0+3][m0 + q].
-        const int q = lane & 15;
-        const int m0 = rb + ((lane >> 4) & 1) * 16;
-        const int k0 = ks * 16 + (lane >> 5) * 8;
-        const E *p0 = lds + (k0 + (q >> 2)) * ld + m0 + 4 * (q & 3);
-        const E *p1 = p0 + 4 * ld;
-        typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p1));
-        s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(Frag, r);
-    }
+    __device__ static inline Frag frag_k(const E *lds, int rb, int ks, int lane, int ld) { return bf16_frag_k(lds, rb, ks, lane, ld); }
+    __device__ static inline Frag frag_m(const E *lds, int rb, int ks, int lane, int ld) { return bf16_frag_m(lds, rb, ks, lane, ld); }
 };
 
 template <int KT> struct Mma<F32, KT> {
@@ -1190,6 +1167,22 @@ hipError_t launch_gemm_updates(int dtype, const GemmArgs *args, int n, const Bia
         if (args[i].zeros == nullptr) return hipErrorInvalidValue;
     return dtype == IST_BF16 ? launch_updates_typed<BF16>(args, n, bias, bias_done, st)
                              : launch_updates_typed<F32>(args, n, bias, bias_done, st);
+}
+
+// Sum of `splits` fp32 partial products laid out [g * splits + sp][M][N] followed by the backward-data epilogue
+// (factor, ReLU mask, storage rounding) into a.C: the finishing pass of a product whose k was split elsewhere.
+hipError_t launch_splitk_finish_bwd(int dtype, const GemmArgs &a, const float *partial, int splits, hipStream_t st)
+{
+    if (a.M <= 0 || a.N <= 0 || a.G <= 0) return hipSuccess;
+    const int esz = dtype == IST_BF16 ? 2 : 4;
+    const bool vecC = vec_c_ok(a, EPI_BWD_DATA, esz);
+    const int64_t units = (int64_t)a.M * ((a.N + 7) / 8);
+    dim3 grid((unsigned)((units + 255) / 256), 1, (unsigned)a.G);
+    if (dtype == IST_BF16)
+        hipLaunchKernelGGL((k_splitk_finish<BF16, EPI_BWD_DATA>), grid, dim3(256), 0, st, a, partial, splits, vecC);
+    else
+        hipLaunchKernelGGL((k_splitk_finish<F32, EPI_BWD_DATA>), grid, dim3(256), 0, st, a, partial, splits, vecC);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm(int dtype, int epi, const GemmArgs &a, hipStream_t st)

@@ -89,6 +89,8 @@ struct ist_ctx {
     size_t off_rowloss = 0, off_bitmap = 0, off_err = 0;  // workspace
     size_t off_partial = 0, partial_bytes = 0, off_zeros = 0;
     bool fused_out = false;   // wide output layer: logits are never stored
+    bool wide_out = false;    // ... and its part of a step runs in the two persistent launches of ist_wideout.hip
+    int32_t wide_nb = 0;      // workgroups per subnet there
     size_t off_pmax = 0, off_psum = 0, off_qmax = 0, off_qsum = 0, off_zlabel = 0, off_lse = 0, off_rsum = 0; int32_t nb_max = 0;
     char *subnets = nullptr;
     char *spare = nullptr;      // second subnet buffer: target of ist_resample, then swapped in
@@ -216,6 +218,27 @@ int gemm_splits(int dtype, int epi, const GemmArgs &a);
 // The EPI_UPDATE products of several layers (independent of each other); small ones share one launch.
 // gemm_update_shares_launch tells which do (the others are better launched, and timed, one by one).
 bool gemm_update_shares_launch(int dtype, const GemmArgs &a);
+
+hipError_t launch_splitk_finish_bwd(int dtype, const GemmArgs &a, const float *partial, int splits, hipStream_t st);
+
+// ---- wide output layer, bf16, at most 128 hidden neurons per subnet and 256 samples: the last layer's part of a
+// local step in two persistent launches that keep the hidden activations in LDS and stream the class tiles of W_t.
+struct WideOutArgs {
+    const void *h; int64_t ldh, gH;          // h_{t-1} [G][B][ldh] in bf16
+    void *W; int64_t gW;                     // W_t blocks [G][N][C], updated in place by the backward launch
+    void *bias; int64_t gBias;               // b_t [G][N] or null, updated in place by the backward launch
+    const int32_t *y; int64_t gY;            // labels [G][B] (stride gY between groups)
+    int32_t G, B, C; int64_t N;              // subnets, samples, hidden width per subnet, classes
+    float alpha, lr_w, lr_b, invB;           // logits factor, step of the weights (lr * factor), step of the bias
+    float *pmax, *psum; int32_t nb;          // statistics launch: per (group, workgroup, sample) max and sum exp
+    float *zlabel;                           // statistics launch: logit of the label [G][B]
+    const float *lse;                        // backward launch: log-sum-exp per sample [G][B]
+    float *partial;                          // backward launch: dh partial sums [G * nb][B][C] fp32
+};
+bool wide_out_supported(int dtype, int32_t B, int64_t C, int64_t N);
+int wide_out_workgroups(int32_t G);          // workgroups per subnet (= nb, = the number of dh partials)
+hipError_t launch_wide_out_stats(const WideOutArgs &a, hipStream_t st);
+hipError_t launch_wide_out_backward(const WideOutArgs &a, hipStream_t st);
 
 hipError_t launch_softmax_xent(const float *logits, const int32_t *y, int64_t y_stride_g,
                                void *dz, float *rowloss, int32_t G, int32_t B, int64_t Cn,
