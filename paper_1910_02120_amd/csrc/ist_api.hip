@@ -790,33 +790,18 @@ ist_status ist_forward_full_static(ist_ctx *ctx, const ist_params *params, const
     return rs;
 }
 
-ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t k, float *loss_out,
-                            void *stream)
+// One local step (step j of k) of every subnet on stream st: forward, loss, backward, update.
+static ist_status one_step(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t j, int32_t k, float *loss_out,
+                           hipStream_t st)
 {
-    if (!ctx) return IST_EINVAL;
-    if (!ctx->bound || !ctx->partitioned) return fail(ctx, IST_ESTATE, "ist_subnet_steps: call ist_partition first");
-    if (!bt || !bt->y) return fail(ctx, IST_EINVAL, "ist_subnet_steps: null batch");
-    if (k < 0) return fail(ctx, IST_EINVAL, "ist_subnet_steps: k < 0");
-    if (bt->B < 1 || bt->B > ctx->max_B) return fail(ctx, IST_ESHAPE, "ist_subnet_steps: B outside 1..max_B");
-    if (bt->stride_s < 0 || bt->stride_k < 0) return fail(ctx, IST_EINVAL, "ist_subnet_steps: negative stride");
     const bool csr = ctx->input == IST_CSR;
-    if (csr) {
-        if (!bt->rowptr || !bt->colidx || !bt->vals || bt->nnz < 0)
-            return fail(ctx, IST_EINVAL, "ist_subnet_steps: incomplete CSR batch");
-    } else if (!bt->x) {
-        return fail(ctx, IST_EINVAL, "ist_subnet_steps: null x");
-    }
-    if (!(lr == lr)) return fail(ctx, IST_EINVAL, "ist_subnet_steps: lr is NaN");
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int t = ctx->t, S = ctx->S, e = ctx->esz(), B = bt->B, dt = ctx->dtype;
     char *ws = ctx->workspace, *sb = ctx->subnets;
     float *rowloss0 = reinterpret_cast<float *>(ws + ctx->off_rowloss);   // [kLossSlots][S][B]
     const int64_t ldb = (B + 7) / 8 * 8;   // row pitch of the transposed dz of a wide output layer
     std::vector<GemmArgs> upd;
     upd.reserve((size_t)t);
-
-
-    for (int j = 0; j < k; ++j) {
+    {
         const int64_t row0 = (int64_t)j * bt->stride_k;
         float *rowloss = rowloss0 + (size_t)(j % kLossSlots) * S * B;
         int out_splits = 1, out_nrb = 0;
@@ -1058,5 +1043,32 @@ ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t
     }
     return IST_OK;
 }
+
+ist_status ist_subnet_steps(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t k, float *loss_out,
+                            void *stream)
+{
+    if (!ctx) return IST_EINVAL;
+    if (!ctx->bound || !ctx->partitioned) return fail(ctx, IST_ESTATE, "ist_subnet_steps: call ist_partition first");
+    if (!bt || !bt->y) return fail(ctx, IST_EINVAL, "ist_subnet_steps: null batch");
+    if (k < 0) return fail(ctx, IST_EINVAL, "ist_subnet_steps: k < 0");
+    if (bt->B < 1 || bt->B > ctx->max_B) return fail(ctx, IST_ESHAPE, "ist_subnet_steps: B outside 1..max_B");
+    if (bt->stride_s < 0 || bt->stride_k < 0) return fail(ctx, IST_EINVAL, "ist_subnet_steps: negative stride");
+    const bool csr = ctx->input == IST_CSR;
+    if (csr) {
+        if (!bt->rowptr || !bt->colidx || !bt->vals || bt->nnz < 0)
+            return fail(ctx, IST_EINVAL, "ist_subnet_steps: incomplete CSR batch");
+    } else if (!bt->x) {
+        return fail(ctx, IST_EINVAL, "ist_subnet_steps: null x");
+    }
+    if (!(lr == lr)) return fail(ctx, IST_EINVAL, "ist_subnet_steps: lr is NaN");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (k == 0) return IST_OK;
+    for (int j = 0; j < k; ++j) {
+        const ist_status rs = one_step(ctx, bt, lr, j, k, loss_out, st);
+        if (rs != IST_OK) return rs;
+    }
+    return IST_OK;
+}
+
 
 }  // extern "C"

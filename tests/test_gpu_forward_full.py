@@ -30,8 +30,6 @@ def _want(P, normalize):
 @pytest.mark.parametrize("name", CASES)
 def test_full_network_logits_match_oracle(name, normalize):
     cfg = SHAPES[name]
-    if normalize and cfg.B == 1:
-        pytest.skip("a batch of one has no variance to standardise by")
     P = H.Problem(cfg, dev="cuda:0", normalize=normalize)
     ctx = P.context()
     got = ctx.forward_full(P.dW, P.db, cfg.B, X=P.dX, csr=P.dcsr)
