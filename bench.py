@@ -37,7 +37,7 @@ EVENT_OVERHEAD_US = 2.4
 
 # HBM bytes per launch of the kernels that can dominate a workload, from two rocprofv3 --pmc runs of
 # this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the 1 GiB
-# copy of --calibrate-copy; the runs and the scale factors are in profiles/.
+# device copies this script starts with; the runs and the scale factors are in profiles/.
 # {workload: {kernel label: bytes}}.  A dominant kernel without an entry is an error: re-measure.
 MEASURED_TRAFFIC = {
     # the three update products of a step and their bias updates in one launch:
@@ -81,9 +81,6 @@ def parse():
     ap.add_argument("--normalize", action="store_true",
                     help="standardise hidden-neuron inputs over the mini-batch (Section 2.2 of the paper); "
                          "off for the headline metric")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="kept for the counter runs: the 1 GiB device copy is now always run first (reference "
-                         "dispatch for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
