@@ -581,13 +581,19 @@ __global__ __launch_bounds__(256) void k_bias_update(BiasArgs a)
 // Wide layers: a workgroup owns 512 columns (8 per lane, one 16-byte load per lane and row), its
 // 4 wavefronts split the batch rows and keep 4 rows in flight each.  Needs a 16-byte aligned
 // dz with a pitch that is a multiple of 8 elements (bf16) / 4 (f32: two loads per row).
+// All wide layers of a step share one launch (blockIdx.z = layer): a single layer's 512-column blocks
+// leave half of the chip idle.
 template <typename D>
-__global__ __launch_bounds__(256) void k_bias_update_wide(BiasJob jb, int32_t B, float lr)
+__global__ __launch_bounds__(256) void k_bias_update_wide(BiasArgs a)
 {
     using T = typename D::T;
     constexpr int V = 8;                       // columns per lane
     constexpr int NV = V * sizeof(T) / 16;     // 16-byte loads per lane and row
     __shared__ float part[3][64][V + 1];
+    const BiasJob jb = a.job[blockIdx.z];
+    const int32_t B = a.B;
+    const float lr = a.lr;
+    if ((int64_t)blockIdx.x * 512 >= jb.ld) return;   // (a whole workgroup: the barrier below is safe)
     const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c0 = ((int64_t)blockIdx.x * 64 + lane) * V;
     float acc[V];
@@ -688,17 +694,23 @@ bool bias_jobs_all_narrow(const BiasArgs &a, int dtype)
 hipError_t launch_bias_update(BiasArgs &a, int dtype, hipStream_t st)
 {
     if (a.njobs <= 0) return hipSuccess;
-    // wide layers go to the 16-byte kernel, one launch each; the rest share one launch
+    // wide layers go to the 16-byte kernel (one launch for all of them); the rest share another launch
+    BiasArgs wide = a;
+    wide.njobs = 0;
     int kept = 0;
+    int64_t widest = 0;
     for (int j = 0; j < a.njobs; ++j) {
         const BiasJob &jb = a.job[j];
-        const bool wide = bias_job_wide(jb, a.B, dtype);
-        if (!wide) { a.job[kept++] = jb; continue; }
-        dim3 grid((unsigned)((jb.ld + 511) / 512), (unsigned)a.G);
+        if (!bias_job_wide(jb, a.B, dtype)) { a.job[kept++] = jb; continue; }
+        wide.job[wide.njobs++] = jb;
+        widest = jb.ld > widest ? jb.ld : widest;
+    }
+    if (wide.njobs > 0) {
+        dim3 grid((unsigned)((widest + 511) / 512), (unsigned)a.G, (unsigned)wide.njobs);
         if (dtype == IST_BF16)
-            hipLaunchKernelGGL(k_bias_update_wide<BF16>, grid, dim3(256), 0, st, jb, a.B, a.lr);
+            hipLaunchKernelGGL(k_bias_update_wide<BF16>, grid, dim3(256), 0, st, wide);
         else
-            hipLaunchKernelGGL(k_bias_update_wide<F32>, grid, dim3(256), 0, st, jb, a.B, a.lr);
+            hipLaunchKernelGGL(k_bias_update_wide<F32>, grid, dim3(256), 0, st, wide);
     }
     a.njobs = kept;
     if (a.njobs <= 0) return hipGetLastError();
