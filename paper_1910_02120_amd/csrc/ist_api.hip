@@ -852,6 +852,7 @@ static ist_status one_step(ist_ctx *ctx, const ist_batch *bt, float lr, int32_t 
                 wa.zlabel = reinterpret_cast<float *>(ws + ctx->off_zlabel);
                 wa.lse = reinterpret_cast<float *>(ws + ctx->off_lse);
                 wa.partial = reinterpret_cast<float *>(ws + ctx->off_partial);
+                wa.zeros = ws + ctx->off_zeros;
                 IST_RUN(KC_GEMM_FWD, launch_wide_out_stats(wa, st), "wide output layer: row statistics");
                 IST_RUN(KC_SOFTMAX_XENT, launch_lse_combine(wa.pmax, wa.psum, wa.nb, reinterpret_cast<float *>(ws + ctx->off_qmax),
                                                            reinterpret_cast<float *>(ws + ctx->off_qsum), wa.zlabel, wa.y, wa.gY, L.R,

@@ -234,6 +234,7 @@ struct WideOutArgs {
     float *zlabel;                           // statistics launch: logit of the label [G][B]
     const float *lse;                        // backward launch: log-sum-exp per sample [G][B]
     float *partial;                          // backward launch: dh partial sums [G * nb][B][C] fp32
+    const void *zeros;                       // 256 zero bytes: what a request outside the matrices reads
 };
 bool wide_out_supported(int dtype, int32_t B, int64_t C, int64_t N);
 int wide_out_workgroups(int32_t G);          // workgroups per subnet (= nb, = the number of dh partials)

@@ -13,7 +13,8 @@
 //               weights being the LDS copy), the bias gradient, and this workgroup's share of dh, which stays
 //               in registers over all its tiles and is written once as an fp32 partial sum (a finishing kernel
 //               adds the workgroups' shares in fixed order and applies the ReLU mask).
-// Workgroup = 8 wavefronts.  Tiles: all B <= 256 samples x 64 classes x all C <= 128 hidden neurons.
+// Workgroup = 8 wavefronts.  Tiles: all B <= 256 samples x 64 classes (statistics) or 32 classes (backward, where
+// four waves make dz of a tile while the other four consume the previous one) x all C <= 128 hidden neurons.
 #include <cstdio>
 
 #include "ist_internal.h"
@@ -36,10 +37,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 // and 4 consecutive rows put an aligned group of 4 chunks into the 4 different 64-byte bank groups.
 __device__ inline int sw16(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }          // 16 chunks per row
 __device__ inline int sw8(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }   //  8 chunks per row (two rows per 256 bytes)
+__device__ inline int sw4(int r) { return (r >> 2) & 3; }                               //  4 chunks per row (four rows per 256 bytes)
 template <int ROWLEN> __device__ inline int tile_off(int r, int e)
 {
-    static_assert(ROWLEN == 128 || ROWLEN == 64, "row lengths in use");
-    const int sw = ROWLEN == 128 ? sw16(r) : sw8(r);
+    static_assert(ROWLEN == 128 || ROWLEN == 64 || ROWLEN == 32, "row lengths in use");
+    const int sw = ROWLEN == 128 ? sw16(r) : (ROWLEN == 64 ? sw8(r) : sw4(r));
     return r * ROWLEN + ((((e >> 3) ^ sw) << 3) | (e & 7));
 }
 // fragments of a swizzled tile: rows rb .. rb + 31, k-step ks, for a tile kept [row][k] / [k][row]
@@ -59,25 +61,13 @@ template <int ROWLEN> __device__ inline bf16x8 frag_m(const uint16_t *t, int rb,
     return __builtin_bit_cast(bf16x8, r);
 }
 
-struct Smem {
+struct SmemStats {
     uint16_t H[kB * kK];         // h_{t-1} of the subnet          [sample][hidden]
     uint16_t W[2][kCT * kK];     // class tiles of W_t              [class][hidden]
-    uint16_t DZ[kB * kCT];       // dz of the tile                  [sample][class]
-    uint16_t Wn[kCT * kK];       // updated weights of the tile, on their way out
-    float lse2[kB];              // log-sum-exp of the sample times log2(e), plus log2 of the batch size
-    int32_t y[kB];
-    float bias[kCT];
-    float dbp[4][kCT];           // bias gradient of the tile in four partial sums over the samples
+    float bias[2][kCT];          // bias of a tile times log2(e); minus infinity past the end of the layer
 };
 
-// 16-byte pieces of a [rows][C] bf16 matrix with row pitch `ld`: piece id -> row id / 16, hidden columns
-// 8 (id % 16) .. +7; rows >= rows_ok and columns >= C read as zero.
-__device__ inline uint4 load_piece(const uint16_t *src, int64_t ld, int id, int64_t row0, int64_t rows_ok, int C)
-{
-    const int r = id >> 4, kc = id & 15;
-    const bool ok = row0 + r < rows_ok && kc * 8 < C;
-    return ok ? *reinterpret_cast<const uint4 *>(src + (row0 + r) * ld + kc * 8) : uint4{0, 0, 0, 0};
-}
+// piece id of a tile of 128-wide rows -> row id / 16, hidden columns 8 (id % 16) .. +7
 __device__ inline void store_piece(uint16_t *tile, int id, uint4 v)
 {
     *reinterpret_cast<uint4 *>(tile + tile_off<kK>(id >> 4, (id & 15) * 8)) = v;
@@ -102,34 +92,56 @@ __device__ inline void logits_tile(const uint16_t *Hs, const uint16_t *Wt, int w
     }
 }
 
-__device__ inline void load_h(Smem &sm, const WideOutArgs &a, int g)
+__device__ inline void load_h(uint16_t *H, const WideOutArgs &a, int g)
 {
     const uint16_t *h = static_cast<const uint16_t *>(a.h) + (int64_t)g * a.gH;
+    const uint16_t *zeros = static_cast<const uint16_t *>(a.zeros);
+    constexpr int kPieces = kB * 16 / kThreads;
+    uint4 v[kPieces];   // all requests first (none behind a branch), then the stores
 #pragma unroll
-    for (int i = 0; i < kB * 16 / kThreads; ++i) {
-        const int id = threadIdx.x + i * kThreads;
-        store_piece(sm.H, id, load_piece(h, a.ldh, id, 0, a.B, a.C));
+    for (int i = 0; i < kPieces; ++i) {
+        const int id = threadIdx.x + i * kThreads, r = id >> 4, kc = id & 15;
+        v[i] = *reinterpret_cast<const uint4 *>(r < a.B && kc * 8 < a.C ? h + (int64_t)r * a.ldh + kc * 8 : zeros);
     }
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) store_piece(H, threadIdx.x + i * kThreads, v[i]);
 }
 
 // ---------------------------------------------------------------- statistics launch
 __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
 {
-    __shared__ Smem sm;
+    __shared__ SmemStats sm;
     const int g = blockIdx.x / a.nb, sp = blockIdx.x % a.nb;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint16_t *W = static_cast<const uint16_t *>(a.W) + (int64_t)g * a.gW;
     const uint16_t *bias = a.bias ? static_cast<const uint16_t *>(a.bias) + (int64_t)g * a.gBias : nullptr;
     const int64_t ntiles = (a.N + kCT - 1) / kCT;
-    load_h(sm, a, g);
+    load_h(sm.H, a, g);
     const int s = 32 * wave + (lane & 31), half = lane >> 5;
     const int label = s < a.B ? a.y[(int64_t)g * a.gY + s] : -1;
     float m_run = -INFINITY, s_run = 0.0f;   // running maximum (times log2(e)) and sum of exp(z - maximum)
     const float alpha2 = a.alpha * kLog2e;
+    // The pieces of the next tile and its bias are requested while this one is worked on.  No branch around a
+    // request and no request that is used where it is issued: one outside the matrices reads a block of zeros, so
+    // the wait counters stay exact and the requests stay in flight over the tile's arithmetic.
+    const uint16_t *zeros = static_cast<const uint16_t *>(a.zeros);
+    auto load_w = [&](int64_t tile, int i) {
+        const int id = threadIdx.x + i * kThreads;
+        const int64_t r = tile * kCT + (id >> 4);
+        const int kc = id & 15;
+        const bool ok = tile < ntiles && r < a.N && kc * 8 < a.C;
+        return *reinterpret_cast<const uint4 *>(ok ? W + r * a.C + kc * 8 : zeros);
+    };
+    auto load_b = [&](int64_t tile) {
+        const int64_t c = tile * kCT + threadIdx.x;
+        const bool ok = threadIdx.x < kCT && bias && tile < ntiles && c < a.N;
+        return *(ok ? bias + c : zeros);
+    };
     uint4 wreg[2];
     int64_t ti = sp;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) wreg[i] = load_piece(W, a.C, threadIdx.x + i * kThreads, ti * kCT, a.N, a.C);
+    for (int i = 0; i < 2; ++i) wreg[i] = load_w(ti, i);
+    uint16_t breg = load_b(ti);
     for (int it = 0; ti < ntiles; ti += a.nb, ++it) {
         const int buf = it & 1;
         const int64_t c0 = ti * kCT;
@@ -138,11 +150,11 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
         // the bias in units of log2(e), and minus infinity for the classes past the end of the layer: the
         // logits then need one multiply-add each and no test (exp2 of minus infinity is zero)
         if (threadIdx.x < kCT)
-            sm.bias[threadIdx.x] = c0 + threadIdx.x < a.N ? (bias ? bf16_to_f32(bias[c0 + threadIdx.x]) * kLog2e : 0.0f) : -INFINITY;
+            sm.bias[buf][threadIdx.x] = c0 + threadIdx.x < a.N ? bf16_to_f32(breg) * kLog2e : -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)   // the next tile's pieces fly during this tile's arithmetic
-            wreg[i] = load_piece(W, a.C, threadIdx.x + i * kThreads, (ti + a.nb) * kCT, a.N, a.C);
-        __syncthreads();
+        for (int i = 0; i < 2; ++i) wreg[i] = load_w(ti + a.nb, i);
+        breg = load_b(ti + a.nb);
+        __syncthreads();   // (one barrier per tile: the W tiles and the bias alternate between two buffers)
         f32x16 acc[2];
         logits_tile<8>(sm.H, sm.W[buf], wave, lane, acc);
         const bool has_label = label >= c0 && label < c0 + kCT;  // rare: one tile in N / 64 per sample
@@ -152,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int cl = 32 * j + 8 * q + 4 * half;
-                const float4 b4 = *reinterpret_cast<const float4 *>(sm.bias + cl);
+                const float4 b4 = *reinterpret_cast<const float4 *>(sm.bias[buf] + cl);
                 const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -179,7 +191,6 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
             s_run = s_run * __builtin_amdgcn_exp2f(m_run - m_new) + se;
             m_run = m_new;
         }
-        __syncthreads();   // the bias is free again (the W tiles alternate between two buffers)
     }
     // the two halves of a row (lane, lane ^ 32), then one pair per sample and workgroup
     const float m_o = __shfl_xor(m_run, 32), s_o = __shfl_xor(s_run, 32);
@@ -195,98 +206,152 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
     }
 }
 
-// ---------------------------------------------------------------- backward launch
+// ---------------------------------------------------------------- backward launch: two groups of waves
+// The exp of the logits is VALU work, the three products that follow are MFMA work, and a SIMD has one pipe of
+// each: with all eight waves in the same phase one pipe idles.  Here the waves form two groups of four (one
+// wave of each group per SIMD).  Group 0 makes dz: in slot s it computes the logits of class tile s (32 classes,
+// all 256 samples), leaves dz in LDS and adds up its share of the bias gradient.  Group 1 consumes the tile one slot
+// later: dW and the updated weights, and the share of dh, which stays in its registers (256 x 128 floats over four
+// waves).  One workgroup barrier per slot; dz and the outgoing weights alternate between two buffers, the W tiles
+// between three (tile s is read by group 0, tile s - 1 by group 1, tile s + 1 arrives).
+constexpr int kC2 = 32;          // classes per tile
+constexpr int kDepth = 2;        // W tiles requested ahead (16 bytes per lane each; 3 would spill registers)
+
+struct SmemBackward {
+    uint16_t H[kB * kK];          // h_{t-1} of the subnet          [sample][hidden]
+    uint16_t W[3][kC2 * kK];      // class tiles of W_t              [class][hidden]
+    uint16_t DZ[2][kB * kC2];     // dz of a tile                    [sample][class]
+    uint16_t Wn[2][kC2 * kK];     // updated weights of a tile, on their way out
+    float lse2[kB];               // log-sum-exp of the sample times log2(e), plus log2 of the batch size
+    int32_t y[kB];
+    float bias2[2][kC2];          // bias of a tile times log2(e); minus infinity past the end of the layer
+    float braw[4][kC2];           // bias of a tile as stored (tiles s - 2 .. s + 1 are alive in slot s)
+    float dbp[4][4][kC2];         // bias gradient of a tile in four partial sums over the samples (tiles s - 2 .. s alive)
+};
+
 __global__ __launch_bounds__(kThreads) void k_wide_out_backward(WideOutArgs a)
 {
-    __shared__ Smem sm;
+    __shared__ SmemBackward sm;
     const int g = blockIdx.x / a.nb, sp = blockIdx.x % a.nb;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // (uniform: scalar registers)
+    const int group = wave >> 2, wg = wave & 3, half = lane >> 5;
     uint16_t *W = static_cast<uint16_t *>(a.W) + (int64_t)g * a.gW;
     uint16_t *bias = a.bias ? static_cast<uint16_t *>(a.bias) + (int64_t)g * a.gBias : nullptr;
-    const int64_t ntiles = (a.N + kCT - 1) / kCT;
-    load_h(sm, a, g);
+    const int64_t ntiles = (a.N + kC2 - 1) / kC2;
+    const int nslots = sp < ntiles ? (int)((ntiles - sp + a.nb - 1) / a.nb) : 0;   // tiles sp, sp + nb, ...
+    auto tile_c0 = [&](int s) { return ((int64_t)sp + (int64_t)s * a.nb) * kC2; };
+    const float alpha2 = a.alpha * kLog2e;
+
+    load_h(sm.H, a, g);
     if (threadIdx.x < kB) {
         const int sx = threadIdx.x;
         sm.lse2[sx] = sx < a.B ? fmaf(a.lse[(int64_t)g * a.B + sx], kLog2e, log2f((float)a.B)) : INFINITY;
         sm.y[sx] = sx < a.B ? a.y[(int64_t)g * a.gY + sx] : -1;
     }
-    const int s = 32 * wave + (lane & 31), half = lane >> 5;
-    f32x16 dh[4];
+    // the bias of class c0 + threadIdx.x of tile s (threads 0 .. 31), requested ahead like the W pieces: a load that is
+    // used in the slot that issues it would make its wave wait for every older request as well
+    // (no branch around a request either: one outside the matrices reads a block of zeros, so the wait counters
+    // stay exact and requests stay in flight across slots)
+    const uint16_t *zeros = static_cast<const uint16_t *>(a.zeros);
+    auto load_b = [&](int s) {
+        const int64_t c = tile_c0(s) + threadIdx.x;
+        const bool ok = threadIdx.x < kC2 && bias && s < nslots && c < a.N;
+        return *(ok ? bias + c : zeros);
+    };
+    auto store_b = [&](int s, uint16_t raw) {   // bias of tile s: in the units of the exponent, and as it is for the update
+        if (threadIdx.x < kC2) {
+            const float b = bf16_to_f32(raw);
+            sm.bias2[s & 1][threadIdx.x] = (s < nslots && tile_c0(s) + threadIdx.x < a.N) ? b * kLog2e : -INFINITY;
+            sm.braw[s & 3][threadIdx.x] = b;
+        }
+    };
+    // one 16-byte piece of a W tile per thread: piece id -> class row id / 16, hidden columns 8 (id % 16) .. +7
+    auto load_w = [&](int s) {
+        const int64_t r = tile_c0(s) + (threadIdx.x >> 4);
+        const int kc = threadIdx.x & 15;
+        const bool ok = s < nslots && r < a.N && kc * 8 < a.C;
+        return *reinterpret_cast<const uint4 *>(ok ? W + r * a.C + kc * 8 : zeros);
+    };
+    store_piece(sm.W[0], threadIdx.x, load_w(0));
+    store_b(0, load_b(0));
+    uint4 wreg[kDepth];   // at the top of slot s: the pieces of tiles s + 1 .. s + kDepth, on their way in
+    uint16_t breg[kDepth];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < kDepth; ++j) { wreg[j] = load_w(1 + j); breg[j] = load_b(1 + j); }
+
+    f32x16 dh[2][4];   // group 1: samples 64 wg + 32 i + lane % 32, hidden 32 j + ...
 #pragma unroll
-        for (int v = 0; v < 16; ++v) dh[j][v] = 0.0f;
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dh[i][j][v] = 0.0f;
     bf16x8 ones;
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
-    const float alpha2 = a.alpha * kLog2e;
 
-    // bias of the class this thread looks after (threads 0 .. 63), as loaded for the tile in progress
-    float b_old = 0.0f;
-    int64_t b_class = -1, prev_c0 = -1;
-    auto finish_tile = [&]() {
-        // b <- b - lr * (the four partial sums, in order); the updated rows of W_t leave as whole 16-byte pieces
-        if (threadIdx.x < kCT && bias && b_class >= 0 && b_class < a.N) {
-            const float db = ((sm.dbp[0][threadIdx.x] + sm.dbp[1][threadIdx.x]) + sm.dbp[2][threadIdx.x]) + sm.dbp[3][threadIdx.x];
-            bias[b_class] = f32_to_bf16(b_old - a.lr_b * db);
-        }
-        if (prev_c0 >= 0) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int id = threadIdx.x + i * kThreads, r = id >> 4, kc = id & 15;
-                if (prev_c0 + r < a.N && kc * 8 < a.C)
-                    *reinterpret_cast<uint4 *>(W + (prev_c0 + r) * a.C + kc * 8) =
-                        *reinterpret_cast<const uint4 *>(sm.Wn + tile_off<kK>(r, kc * 8));
-            }
+    // the rows of tile s leave (whole 16-byte pieces) and its bias is updated: b <- b - lr * (four sums, in order)
+    auto finish_tile = [&](int s) {
+        const int64_t c0 = tile_c0(s);
+        const int r = threadIdx.x >> 4, kc = threadIdx.x & 15;
+        if (c0 + r < a.N && kc * 8 < a.C)
+            *reinterpret_cast<uint4 *>(W + (c0 + r) * a.C + kc * 8) =
+                *reinterpret_cast<const uint4 *>(sm.Wn[s & 1] + tile_off<kK>(r, kc * 8));
+        if (threadIdx.x < kC2 && bias && c0 + threadIdx.x < a.N) {
+            const float(&p)[4][kC2] = sm.dbp[s & 3];
+            const float db = ((p[0][threadIdx.x] + p[1][threadIdx.x]) + p[2][threadIdx.x]) + p[3][threadIdx.x];
+            bias[c0 + threadIdx.x] = f32_to_bf16(sm.braw[s & 3][threadIdx.x] - a.lr_b * db);
         }
     };
+    __syncthreads();   // h, lse, labels, the first W tile and its bias are visible
 
-    uint4 wreg[2];
-    int64_t ti = sp;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) wreg[i] = load_piece(W, a.C, threadIdx.x + i * kThreads, ti * kCT, a.N, a.C);
-    if (ti < ntiles) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) store_piece(sm.W[0], threadIdx.x + i * kThreads, wreg[i]);
-    }
-    for (int it = 0; ti < ntiles; ti += a.nb, ++it) {
-        const int buf = it & 1;
-        const int64_t c0 = ti * kCT;
-        const uint16_t *Wt = sm.W[buf];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)   // the next tile's pieces fly during this tile's arithmetic
-            wreg[i] = load_piece(W, a.C, threadIdx.x + i * kThreads, (ti + a.nb) * kCT, a.N, a.C);
-        finish_tile();                // of the tile before (complete since the barrier that ended it)
-        prev_c0 = c0;
-        if (threadIdx.x < kCT) {
-            b_class = c0 + threadIdx.x;
-            b_old = (bias && b_class < a.N) ? bf16_to_f32(bias[b_class]) : 0.0f;
-            sm.bias[threadIdx.x] = b_class < a.N ? b_old * kLog2e : -INFINITY;
-        }
-        __syncthreads();   // B1: bias (and, the first time, h, lse, labels and the first W tile) visible
-        // ---- logits -> dz (bf16) -> LDS ----
-        {
+    // Slot s, both groups: tile s + 1 goes into its LDS buffer (which held tile s - 2), tile s + 1 + kDepth is requested
+    // into the registers that this frees, tile s - 2 leaves.  wr / br: the registers of tiles s + 1, s + 1 + kDepth, ...
+    auto move_tiles = [&](int s, uint4 &wr, uint16_t &br) {
+        store_piece(sm.W[(s + 1) % 3], threadIdx.x, wr);
+        store_b(s + 1, br);
+        wr = load_w(s + 1 + kDepth);
+        br = load_b(s + 1 + kDepth);
+        if (s >= 2 && s - 2 < nslots) finish_tile(s - 2);
+    };
+    // group 0 in slot s: logits of tile s -> dz (bf16) -> LDS; wave wg: samples 64 wg .. 64 wg + 63
+    auto produce = [&](int s) {
+        if (s < nslots) {
+            const uint16_t *Wt = sm.W[s % 3];
+            const int64_t c0 = tile_c0(s);
             f32x16 acc[2];
-            logits_tile<2>(sm.H, Wt, wave, lane, acc);
-            // dz = exp2(z2 - lse2 - log2 B) with z2 = alpha2 acc + bias2 in units of log2(e); classes past the end
-            // of the layer carry a bias of minus infinity and samples past the batch a log-sum-exp of plus
-            // infinity, so they come out as exact zeros without a test; the label's 1 / B is taken off in a
-            // branch that few tiles enter (a sample's label lies in one tile of N / 64)
-            const float ls = sm.lse2[s];
-            const int label = sm.y[s];
-            const bool has_label = label >= c0 && label < c0 + kCT;
-            const bool any_label = __builtin_amdgcn_ballot_w64(has_label) != 0ull;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+#pragma unroll 4
+            for (int ks = 0; ks < kK / 16; ++ks) {
+                const bf16x8 fb = frag_k<kK>(Wt, 0, ks, lane);
+                const bf16x8 fa0 = frag_k<kK>(sm.H, 64 * wg, ks, lane);
+                const bf16x8 fa1 = frag_k<kK>(sm.H, 64 * wg + 32, ks, lane);
+                acc[0] = bf16_mma(fb, fa0, acc[0]);
+                acc[1] = bf16_mma(fb, fa1, acc[1]);
+            }
+            // dz = exp2(z2 - lse2 - log2 B) (see k_wide_out_backward: masks through the bias and the
+            // log-sum-exp, the label's 1 / B in a branch that few tiles enter)
+            uint16_t *DZ = sm.DZ[s & 1];
+            const float *b2 = sm.bias2[s & 1];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = 64 * wg + 32 * i + (lane & 31);
+                const float ls = sm.lse2[row];
+                const int label = sm.y[row];
+                const bool has_label = label >= c0 && label < c0 + kC2;
+                const bool any_label = __builtin_amdgcn_ballot_w64(has_label) != 0ull;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int cl = 32 * j + 8 * q + 4 * half;
-                    const float4 b4 = *reinterpret_cast<const float4 *>(sm.bias + cl);
+                    const int cl = 8 * q + 4 * half;
+                    const float4 b4 = *reinterpret_cast<const float4 *>(b2 + cl);
                     const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
                     float d[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        d[u] = __builtin_amdgcn_exp2f(fmaf(alpha2, acc[j][4 * q + u], bb[u]) - ls);
+                        d[u] = __builtin_amdgcn_exp2f(fmaf(alpha2, acc[i][4 * q + u], bb[u]) - ls);
                     if (any_label) {
 #pragma unroll
                         for (int u = 0; u < 4; ++u) d[u] = (c0 + cl + u == label) ? d[u] - a.invB : d[u];
@@ -294,66 +359,101 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_backward(WideOutArgs a)
                     uint2 o;
                     o.x = f32x2_to_bf16x2(d[0], d[1]);
                     o.y = f32x2_to_bf16x2(d[2], d[3]);
-                    *reinterpret_cast<uint2 *>(sm.DZ + tile_off<kCT>(s, cl)) = o;
+                    *reinterpret_cast<uint2 *>(DZ + tile_off<kC2>(row, cl)) = o;
                 }
+            }
+            // the wave's share of the bias gradient: the sum of its 64 samples' dz as stored, per class - a product
+            // with a block of ones over the k-steps it has just written (the LDS keeps a wave's accesses in order)
+            f32x16 dbv;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dbv[v] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dbv = bf16_mma(ones, frag_m<kC2>(DZ, 0, 4 * wg + j, lane), dbv);
+            if (half == 0) sm.dbp[s & 3][wg][lane & 31] = dbv[0];
         }
-        // the next W tile into the other buffer (last read before the barrier that ended the tile before)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) store_piece(sm.W[buf ^ 1], threadIdx.x + i * kThreads, wreg[i]);
-        __syncthreads();   // B2: dz tile complete
-        // ---- dW block (32 classes x 32 hidden per wave, k = samples), the bias gradient of those classes
-        //      (a product with a block of ones, every fourth k-step per wave), the updated weights -> LDS ----
+    };
+    // group 1 in slot s: tile t = s - 1
+    auto consume = [&](int t) {
+        // ---- dW block of wave wg (32 classes x hidden 32 wg .. +31, k = samples), the updated weights -> LDS ----
+        const uint16_t *Wt = sm.W[t % 3];
+        const uint16_t *DZ = sm.DZ[t & 1];
         {
-            const int ci = wave >> 2, hj = wave & 3;
-            f32x16 dw, dbv;
+            f32x16 dw;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { dw[v] = 0.0f; dbv[v] = 0.0f; }
+            for (int v = 0; v < 16; ++v) dw[v] = 0.0f;
 #pragma unroll 4
             for (int ks = 0; ks < kB / 16; ++ks) {
-                const bf16x8 fa = frag_m<kCT>(sm.DZ, 32 * ci, ks, lane);   // rows = classes, k = samples
-                const bf16x8 fb = frag_m<kK>(sm.H, 32 * hj, ks, lane);     // rows = hidden,  k = samples
+                const bf16x8 fa = frag_m<kC2>(DZ, 0, ks, lane);          // rows = classes, k = samples
+                const bf16x8 fb = frag_m<kK>(sm.H, 32 * wg, ks, lane);   // rows = hidden,  k = samples
                 dw = bf16_mma(fb, fa, dw);
-                if ((ks & 3) == hj) dbv = bf16_mma(ones, fa, dbv);
             }
-            const int cl = 32 * ci + (lane & 31);
-            if (half == 0) sm.dbp[hj][cl] = dbv[0];
+            const int cl = lane & 31;
+            uint16_t *Wn = sm.Wn[t & 1];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int jj = 32 * hj + 8 * q + 4 * half;
-                const int o = tile_off<kK>(cl, jj);
+                const int o = tile_off<kK>(cl, 32 * wg + 8 * q + 4 * half);
                 const uint2 old = *reinterpret_cast<const uint2 *>(Wt + o);
                 const float w0 = __uint_as_float(old.x << 16), w1 = __uint_as_float(old.x & 0xffff0000u);
                 const float w2 = __uint_as_float(old.y << 16), w3 = __uint_as_float(old.y & 0xffff0000u);
                 uint2 nw;
                 nw.x = f32x2_to_bf16x2(w0 - a.lr_w * dw[4 * q], w1 - a.lr_w * dw[4 * q + 1]);
                 nw.y = f32x2_to_bf16x2(w2 - a.lr_w * dw[4 * q + 2], w3 - a.lr_w * dw[4 * q + 3]);
-                *reinterpret_cast<uint2 *>(sm.Wn + o) = nw;
+                *reinterpret_cast<uint2 *>(Wn + o) = nw;
             }
         }
-        // ---- this workgroup's share of dh: 32 samples x 128 hidden per wave, k = the tile's classes, old W ----
-#pragma unroll 2
-        for (int ks = 0; ks < kCT / 16; ++ks) {
-            const bf16x8 fa = frag_k<kCT>(sm.DZ, 32 * wave, ks, lane);       // rows = samples, k = classes
+        // ---- share of dh: samples 64 wg .. 64 wg + 63 x 128 hidden, k = the tile's 32 classes, old W ----
+#pragma unroll
+        for (int ks = 0; ks < kC2 / 16; ++ks) {
+            const bf16x8 fa0 = frag_k<kC2>(DZ, 64 * wg, ks, lane);        // rows = samples, k = classes
+            const bf16x8 fa1 = frag_k<kC2>(DZ, 64 * wg + 32, ks, lane);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bf16x8 fb = frag_m<kK>(Wt, 32 * j, ks, lane);          // rows = hidden,  k = classes
-                dh[j] = bf16_mma(fb, fa, dh[j]);
+                const bf16x8 fb = frag_m<kK>(Wt, 32 * j, ks, lane);       // rows = hidden,  k = classes
+                dh[0][j] = bf16_mma(fb, fa0, dh[0][j]);
+                dh[1][j] = bf16_mma(fb, fa1, dh[1][j]);
             }
         }
-        __syncthreads();   // B3: everybody is done with the dz tile and this W tile; Wn and the partial sums are written
-    }
-    finish_tile();
-    if (s < a.B) {
-        float *out = a.partial + (((int64_t)g * a.nb + sp) * a.B + s) * a.C;
+    };
+    // Slots 0 .. nslots + 1 (the last two only finish tiles), in groups of kDepth so that every slot names its registers.
+    // The two groups run loops of their own - what one keeps in registers is not alive in the other - with the same
+    // number of workgroup barriers, one at the end of every slot.
+    const int nloop = nslots + 2;
+    if (group == 0) {
+        for (int s0 = 0; s0 < nloop; s0 += kDepth) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int jj = 32 * j + 8 * q + 4 * half;
-                if (jj < a.C)
-                    *reinterpret_cast<float4 *>(out + jj) =
-                        make_float4(dh[j][4 * q], dh[j][4 * q + 1], dh[j][4 * q + 2], dh[j][4 * q + 3]);
+            for (int j = 0; j < kDepth; ++j) {
+                move_tiles(s0 + j, wreg[j], breg[j]);
+                produce(s0 + j);
+                __syncthreads();
             }
+        }
+        return;
+    }
+    for (int s0 = 0; s0 < nloop; s0 += kDepth) {
+#pragma unroll
+        for (int j = 0; j < kDepth; ++j) {
+            move_tiles(s0 + j, wreg[j], breg[j]);
+            if (s0 + j >= 1 && s0 + j - 1 < nslots) consume(s0 + j - 1);
+            __syncthreads();
+        }
+    }
+    {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = 64 * wg + 32 * i + (lane & 31);
+            if (row < a.B) {
+                float *out = a.partial + (((int64_t)g * a.nb + sp) * a.B + row) * a.C;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int jj = 32 * j + 8 * q + 4 * half;
+                        if (jj < a.C)
+                            *reinterpret_cast<float4 *>(out + jj) =
+                                make_float4(dh[i][j][4 * q], dh[i][j][4 * q + 1], dh[i][j][4 * q + 2], dh[i][j][4 * q + 3]);
+                    }
+            }
+        }
     }
 }
 
@@ -381,7 +481,7 @@ int wide_out_workgroups(int32_t G)
 
 hipError_t launch_wide_out_stats(const WideOutArgs &a, hipStream_t st)
 {
-    if (!args_ok(a) || !a.pmax || !a.psum || !a.zlabel) return hipErrorInvalidValue;
+    if (!args_ok(a) || !a.pmax || !a.psum || !a.zlabel || !a.zeros) return hipErrorInvalidValue;
     char label[64];
     snprintf(label, sizeof(label), "k_wide_out_stats_bf16_c%d", (int)a.C);
     tag_kernel(label, 2.0 * a.B * (double)a.N * a.C * a.G, (double)a.G * ((double)a.N * a.C + (double)a.B * a.C) * 2.0);
@@ -391,7 +491,7 @@ hipError_t launch_wide_out_stats(const WideOutArgs &a, hipStream_t st)
 
 hipError_t launch_wide_out_backward(const WideOutArgs &a, hipStream_t st)
 {
-    if (!args_ok(a) || !a.lse || !a.partial) return hipErrorInvalidValue;
+    if (!args_ok(a) || !a.lse || !a.partial || !a.zeros) return hipErrorInvalidValue;
     char label[64];
     snprintf(label, sizeof(label), "k_wide_out_backward_bf16_c%d", (int)a.C);
     // logits again, dW and dh: three products of 2 B N C flops; W read and written once
