@@ -32,9 +32,11 @@
 #include "ist_bias_block.h"
 #include "ist_mfma.h"
 
+#include <cmath>
 #include <cstdio>
 
 namespace ist {
+
 
 
 template <typename D, int KT> struct Mma;   // KT: k extent of one LDS tile
@@ -264,6 +266,14 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
         }
         return;
     }
+    if (EPI == EPI_UPDATE_ACC) {
+        // the accumulators started at -w / lr: w - lr dW = 0 - lr acc (the subtraction from +0 keeps a zero weight
+        // with a zero gradient at +0); chunks are whole here (the launcher takes this path for N % 8 == 0 only)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) val[i] = 0.0f - a.lr * val[i];
+        Row8<T>::st(static_cast<T *>(a.C) + ci, vec, nv, val);
+        return;
+    }
     float o[8];
     if (EPI == EPI_BWD_DATA) {
         if (HASPRE && vec) pre8_decode<T>(pre, o);
@@ -386,7 +396,15 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
     constexpr int RPP = 64 / CPR;
     constexpr int NP = 32 / RPP;
     using T = typename D::T;
-    constexpr bool PRE = (EPI == EPI_UPDATE || EPI == EPI_BWD_DATA);
+    // ACCW: the update product with the old weights folded into the accumulators.  The weights of a tile are
+    // requested while the previous tile's epilogue runs (into registers that the main loop needs, but no epilogue)
+    // and become the accumulators' starting value -w / lr; the epilogue then has nothing to wait for:
+    // w - lr dW = -lr (-w / lr + dW).  Without it every workgroup's epilogue waits for 128 KB of weights while
+    // its MFMA pipe idles.  (fp32 throughout: the detour through w / lr moves a result by about 2^-22 of w,
+    // against bf16's half unit in the last place of 2^-9; a weight with a zero gradient keeps its bits.)
+    constexpr bool ACCW = (EPI == EPI_UPDATE_ACC);
+    static_assert(!ACCW || (PERSIST && DB && KG == 1 && D::kBytes == 2), "configuration of the accumulator-resident update");
+    constexpr bool PRE = (EPI == EPI_UPDATE || EPI == EPI_BWD_DATA || ACCW);
     constexpr int PD = !PRE ? 1 : (DB ? TM : ((D::kBytes == 2 && !PERSIST) ? 2 : 1));
     // Old weights (update) / activations (ReLU mask) of the chunks this lane will finish in row slice i of the
     // tile at (tg, tm0, tn0), as raw 16-byte pieces.
@@ -396,7 +414,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
             const int m = tm0 + wm + i * 32 + p * RPP + lane / CPR;
             const int n = tn0 + wn + 8 * (lane % CPR);
             const bool ok = vecC && kg == 0 && m < a.M && n + 8 <= a.N;
-            const T *src = EPI == EPI_UPDATE
+            const T *src = (EPI == EPI_UPDATE || ACCW)
                                ? static_cast<const T *>(a.C) + (int64_t)tg * a.gC + (int64_t)m * a.ldc + n
                                : static_cast<const T *>(a.mask) + (int64_t)tg * a.gMask + (int64_t)m * a.ldm + n;
             const uint4 *q = reinterpret_cast<const uint4 *>(ok ? src : reinterpret_cast<const T *>(Z));
@@ -450,14 +468,50 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
         }
     };
     prologue();
+    if constexpr (ACCW) {
+#pragma unroll
+        for (int d = 0; d < TM; ++d) preload(d, pre[d], g, m0, n0);
+    }
 
     for (;;) {
+        if constexpr (ACCW) {
+            // accumulators <- -w / lr.  The weights came as whole 16-byte row pieces (8 columns of a row per lane);
+            // the accumulator layout wants 4 consecutive columns of row lane % 32 per register quad: through the
+            // wave's own staging rows, as bf16 (row pitch 68 elements: 8-byte accesses, no two of the 32 rows
+            // on the same bank pair).
+            constexpr int LD16 = 32 * TN + 4;
+            uint16_t *st16 = reinterpret_cast<uint16_t *>(fsm + w4 * (32 * LDC));
+            const float ninv = -1.0f / a.lr;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    uint16_t *dst = st16 + (p * RPP + lane / CPR) * LD16 + 8 * (lane % CPR);
+                    *reinterpret_cast<uint2 *>(dst) = make_uint2(pre[i][p].v[0].x, pre[i][p].v[0].y);
+                    *reinterpret_cast<uint2 *>(dst + 4) = make_uint2(pre[i][p].v[0].z, pre[i][p].v[0].w);
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint2 w = *reinterpret_cast<const uint2 *>(st16 + (lane & 31) * LD16 + 32 * j + 8 * q + 4 * (lane >> 5));
+                        acc[i][j][4 * q] = ninv * __uint_as_float(w.x << 16);
+                        acc[i][j][4 * q + 1] = ninv * __uint_as_float(w.x & 0xffff0000u);
+                        acc[i][j][4 * q + 2] = ninv * __uint_as_float(w.y << 16);
+                        acc[i][j][4 * q + 3] = ninv * __uint_as_float(w.y & 0xffff0000u);
+                    }
+            }
+            __syncthreads();   // every wave is done with its staging rows (this and the last epilogue) before operand tiles land there
+        } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        }
         const int ntile = (kend - kbeg + KT - 1) / KT;
 
         if (DB) {
@@ -665,7 +719,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
         // The old weights / activations are fetched PD row slices ahead: the loads are independent of the
         // stores of earlier chunks, which the compiler cannot know, and would otherwise each wait out a full
         // memory round trip.
-        if (PRE) {
+        if (PRE && !ACCW) {
 #pragma unroll
             for (int d = 0; d < PD; ++d)
                 if (d < TM) preload(d, pre[d], cg, cm0, cn0);
@@ -708,16 +762,19 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
                             if (ch == 0 && m < a.M && blk < a.nb) a.pmax[((int64_t)cg * a.nb + blk) * a.M + m] = s;
                         }
                     } else
-                        epi8<D, EPI, PRE>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
-                                          val, vecC, bias8, pre[i % PD][p]);
+                        epi8<D, EPI, PRE && !ACCW>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
+                                                   val, vecC, bias8, ACCW ? Pre8<T>{} : pre[i % PD][p]);
                 }
             }
-            if (PRE && i + PD < TM) preload(i + PD, pre[i % PD], cg, cm0, cn0);
+            if (PRE && !ACCW && i + PD < TM) preload(i + PD, pre[i % PD], cg, cm0, cn0);
+            // the next tile's weights, slice by slice as the accumulators of this tile's slices retire (a last tile
+            // asks for its own weights again and drops them)
+            if constexpr (ACCW) preload(i, pre[i], g, m0, n0);
         }
         }
         if (!more) break;
         t = tn;
-        __syncthreads();   // staging reads are done before the next tile's LDS stores
+        if (!ACCW) __syncthreads();   // staging reads are done before the next tile's LDS stores
     }
 }
 
@@ -963,7 +1020,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
 {
     const int esz = D::kBytes;
     const bool vecC = vec_c_ok(a, EPI, esz);
-    static const char *const kEpi[] = {"fwd_relu", "fwd_logits", "bwd_data", "update", "partial", "fwd_lse", "fwd_dzt"};
+    static const char *const kEpi[] = {"fwd_relu", "fwd_logits", "bwd_data", "update", "partial", "fwd_lse", "fwd_dzt", "update"};
     static thread_local char lab[40];
     snprintf(lab, sizeof(lab), "%s_%s%s", kEpi[EPI], esz == 2 ? "bf16" : "f32", VEC ? "" : "_novec");
     s_label = lab;
@@ -996,8 +1053,15 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
         if constexpr (D::kBytes == 2 && EPI == EPI_UPDATE) {
             // wide layers: one persistent 256x256 workgroup per CU, started in 4 phase groups
             if (!done && a.K >= 256 && (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 1024) {
-                launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, true, true>, 512, a, vecC,
-                                       1, a.K, st, true, 256, 4, 1);
+                // weights in whole 16-byte pieces and a usable 1 / lr: the old weights ride in the accumulators
+                bool in_acc = false;
+                if constexpr (VEC) in_acc = vecC && a.N % 8 == 0 && a.lr != 0.0f && std::isfinite(1.0f / a.lr);
+                if constexpr (VEC) if (in_acc)
+                    launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI_UPDATE_ACC, 256, 256, 2, 4, 1, 1, VEC, 64, true, true>, 512,
+                                           a, vecC, 1, a.K, st, true, 256, 4, 1);
+                if (!in_acc)
+                    launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, true, true>, 512, a, vecC,
+                                           1, a.K, st, true, 256, 4, 1);
                 done = true;
             }
         }

@@ -171,9 +171,10 @@ hipError_t launch_export(const void *sub, void *dst, int64_t nr, int64_t nc, int
 enum Epilogue {
     EPI_FWD_RELU = 0, EPI_FWD_LOGITS = 1, EPI_BWD_DATA = 2, EPI_UPDATE = 3, EPI_PARTIAL = 4,
     EPI_LSE = 5,   // logits are not stored: per row and column block, max and sum of exp (wide output layers)
-    EPI_DZT = 6    // logits recomputed with the roles of the operands exchanged (rows = classes, columns = samples):
+    EPI_DZT = 6,   // logits recomputed with the roles of the operands exchanged (rows = classes, columns = samples):
                    // store dz^T[n][b] = (exp(z[b][n] - lse[b]) - [n == y_b]) / B in the storage dtype.  A tile of
                    // dz^T is one contiguous piece of memory; a tile of dz [b][n] would be 128 pieces 2 N_t bytes apart
+    EPI_UPDATE_ACC = 7   // EPI_UPDATE whose accumulators start at -w / lr (chosen by the launcher, not by callers)
 };
 
 // C[g][m][n] (+)= sum_k A_g(m,k) * B_g(n,k), element (m,k) of A at A + g*gA + m*sam + k*sak.

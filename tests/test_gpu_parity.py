@@ -36,6 +36,9 @@ SHAPES = {
     # wide enough for the 256x256 block tiles (forward of layer 1, backward-data of layer 2)
     "big-tiles-bf16": _mk("big-tiles-bf16", "cfg3", dims=(520, 33280, 4352, 10), S=16, B=300, k=2,
                           lr=0.05),
+    # the update product of a layer with at least 1024 blocks of 256 x 256 (persistent kernel that keeps the old
+    # weights in its accumulators): 5808 = 22 x 256 + 176 rows and columns per subnet, 264 = 4 x 64 + 8 samples
+    "wide-update-bf16": _mk("wide-update-bf16", "cfg3", dims=(264, 11616, 11616, 10), S=2, B=264, k=2, lr=0.05),
     # degenerate shapes: one hidden layer and a batch of one sample; a deeper net with S = N_l / 2
     "one-hidden-B1-f32": _mk("one-hidden-B1-f32", "cfg2", dims=(40, 64, 7), S=4, B=1, k=2, lr=0.05),
     "deep-bf16": _mk("deep-bf16", "cfg3", dims=(64, 128, 256, 128, 64, 12), S=4, B=20, k=3, lr=0.05),
