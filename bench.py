@@ -44,17 +44,17 @@ MEASURED_TRAFFIC = {
     # read 77.05 MB (FETCH_SIZE 37623.1 KiB x 2.000) + written 34.16 MB (WRITE_SIZE 33360.7 KiB x 1.000)
     "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3_bias": 111.21e6},
     "cfg4": {
-        # read 1642.8 MB (802173.7 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000), average of the three layers
-        "gemm_update_bf16_256x256_t512_persistent": 2537.6e6,
-        # read 1365.9 MB + written 67.1 MB
-        "gemm_fwd_relu_bf16_256x256_t512": 1433.0e6,
-        # read 1678.1 MB + written 67.1 MB
+        # read 1707.7 MB (833881.1 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000), average of the three layers
+        "gemm_update_bf16_256x256_t512_persistent": 2602.5e6,
+        # read 1381.1 MB + written 67.1 MB
+        "gemm_fwd_relu_bf16_256x256_t512": 1448.2e6,
+        # read 1678.0 MB + written 67.1 MB
         "gemm_bwd_data_bf16_256x256_t512": 1745.2e6,
     },
     "cfg5": {
-        # backward launch of the wide output layer: read 1396.9 MB (682097.2 KiB x 2.000) + written 1419.0 MB
-        # (1385714.6 KiB x 1.000): W_t read once and written once
-        "k_wide_out_backward_bf16_c128": 2815.9e6,
+        # backward launch of the wide output layer: read 1407.7 MB (687385.7 KiB x 2.000) + written 1421.3 MB
+        # (1388001.0 KiB x 1.000): W_t read once and written once
+        "k_wide_out_backward_bf16_c128": 2829.0e6,
         # statistics launch: read 1396.8 MB, written 0.6 MB
         "k_wide_out_stats_bf16_c128": 1397.4e6,
     },
