@@ -211,8 +211,10 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
 // each: with all eight waves in the same phase one pipe idles.  Here the waves form two groups of four (one
 // wave of each group per SIMD).  Group 0 makes dz: in slot s it computes the logits of class tile s (32 classes,
 // all 256 samples), leaves dz in LDS and adds up its share of the bias gradient.  Group 1 consumes the tile one slot
-// later: dW and the updated weights, and the share of dh, which stays in its registers (256 x 128 floats over four
-// waves).  One workgroup barrier per slot; dz and the outgoing weights alternate between two buffers, the W tiles
+// later: dW and the updated weights.  The workgroup's share of dh stays in registers over all its tiles, 32 samples
+// x 128 hidden neurons per wave: a wave of group 0 adds the tile's term for the first 32 of its 64 samples right after
+// writing their dz, its partner in group 1 the term for the other 32 one slot later (with all of dh in group 1 that
+// group's chain of dependent LDS reads and MFMAs set the pace).  One workgroup barrier per slot; dz and the outgoing weights alternate between two buffers, the W tiles
 // between three (tile s is read by group 0, tile s - 1 by group 1, tile s + 1 arrives).
 constexpr int kC2 = 32;          // classes per tile
 constexpr int kDepth = 2;        // W tiles requested ahead (16 bytes per lane each; 3 would spill registers)
@@ -279,13 +281,25 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_backward(WideOutArgs a)
 #pragma unroll
     for (int j = 0; j < kDepth; ++j) { wreg[j] = load_w(1 + j); breg[j] = load_b(1 + j); }
 
-    f32x16 dh[2][4];   // group 1: samples 64 wg + 32 i + lane % 32, hidden 32 j + ...
+    // the wave's share of dh: samples 64 wg + 32 group + lane % 32 (the lower half of a wave pair's 64 samples with
+    // group 0, which adds to it right after making dz, the upper half with group 1), hidden 32 j + ...
+    f32x16 dh[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int v = 0; v < 16; ++v) dh[j][v] = 0.0f;
+    // dh rows += dz (32 samples from row0 on, the tile's 32 classes) x old W of the tile
+    auto add_dh = [&](const uint16_t *DZ, const uint16_t *Wt, int row0) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dh[i][j][v] = 0.0f;
+        for (int ks = 0; ks < kC2 / 16; ++ks) {
+            const bf16x8 fa = frag_k<kC2>(DZ, row0, ks, lane);            // rows = samples, k = classes
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bf16x8 fb = frag_m<kK>(Wt, 32 * j, ks, lane);       // rows = hidden,  k = classes
+                dh[j] = bf16_mma(fb, fa, dh[j]);
+            }
+        }
+    };
     bf16x8 ones;
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
@@ -370,6 +384,8 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_backward(WideOutArgs a)
 #pragma unroll
             for (int j = 0; j < 4; ++j) dbv = bf16_mma(ones, frag_m<kC2>(DZ, 0, 4 * wg + j, lane), dbv);
             if (half == 0) sm.dbp[s & 3][wg][lane & 31] = dbv[0];
+            // and its share of dh, from the 32 rows of dz that this wave wrote first
+            add_dh(DZ, Wt, 64 * wg);
         }
     };
     // group 1 in slot s: tile t = s - 1
@@ -401,18 +417,8 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_backward(WideOutArgs a)
                 *reinterpret_cast<uint2 *>(Wn + o) = nw;
             }
         }
-        // ---- share of dh: samples 64 wg .. 64 wg + 63 x 128 hidden, k = the tile's 32 classes, old W ----
-#pragma unroll
-        for (int ks = 0; ks < kC2 / 16; ++ks) {
-            const bf16x8 fa0 = frag_k<kC2>(DZ, 64 * wg, ks, lane);        // rows = samples, k = classes
-            const bf16x8 fa1 = frag_k<kC2>(DZ, 64 * wg + 32, ks, lane);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bf16x8 fb = frag_m<kK>(Wt, 32 * j, ks, lane);       // rows = hidden,  k = classes
-                dh[0][j] = bf16_mma(fb, fa0, dh[0][j]);
-                dh[1][j] = bf16_mma(fb, fa1, dh[1][j]);
-            }
-        }
+        // ---- share of dh: the upper 32 of the wave pair's samples (the lower 32 were added by group 0) ----
+        add_dh(DZ, Wt, 64 * wg + 32);
     };
     // Slots 0 .. nslots + 1 (the last two only finish tiles), in groups of kDepth so that every slot names its registers.
     // The two groups run loops of their own - what one keeps in registers is not alive in the other - with the same
@@ -427,33 +433,28 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_backward(WideOutArgs a)
                 __syncthreads();
             }
         }
-        return;
-    }
-    for (int s0 = 0; s0 < nloop; s0 += kDepth) {
+    } else {
+        for (int s0 = 0; s0 < nloop; s0 += kDepth) {
 #pragma unroll
-        for (int j = 0; j < kDepth; ++j) {
-            move_tiles(s0 + j, wreg[j], breg[j]);
-            if (s0 + j >= 1 && s0 + j - 1 < nslots) consume(s0 + j - 1);
-            __syncthreads();
-        }
-    }
-    {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int row = 64 * wg + 32 * i + (lane & 31);
-            if (row < a.B) {
-                float *out = a.partial + (((int64_t)g * a.nb + sp) * a.B + row) * a.C;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int jj = 32 * j + 8 * q + 4 * half;
-                        if (jj < a.C)
-                            *reinterpret_cast<float4 *>(out + jj) =
-                                make_float4(dh[i][j][4 * q], dh[i][j][4 * q + 1], dh[i][j][4 * q + 2], dh[i][j][4 * q + 3]);
-                    }
+            for (int j = 0; j < kDepth; ++j) {
+                move_tiles(s0 + j, wreg[j], breg[j]);
+                if (s0 + j >= 1 && s0 + j - 1 < nslots) consume(s0 + j - 1);
+                __syncthreads();
             }
         }
+    }
+    const int row = 64 * wg + 32 * group + (lane & 31);
+    if (row < a.B) {
+        float *out = a.partial + (((int64_t)g * a.nb + sp) * a.B + row) * a.C;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int jj = 32 * j + 8 * q + 4 * half;
+                if (jj < a.C)
+                    *reinterpret_cast<float4 *>(out + jj) =
+                        make_float4(dh[j][4 * q], dh[j][4 * q + 1], dh[j][4 * q + 2], dh[j][4 * q + 3]);
+            }
     }
 }
 

@@ -360,7 +360,7 @@ def _factors(cfg, paper):
     ("csr-f32", False, False), ("wide-out-f32", False, False), ("many-steps-f32", False, False),
     ("mid-out-bf16", False, False), ("deep-bf16", False, False), ("speech-small", False, False),
     ("cfg4-small", True, True), ("ragged-f32", False, True), ("cfg5-small", False, True),
-    ("uneven-S5-bf16", True, False), ("uneven-S3-f32", False, False)])
+    ("uneven-S5-bf16", True, False), ("uneven-S3-f32", False, False), ("wide-update-bf16", False, False)])
 def test_k_local_steps_with_layer_factors_match_oracle(name, paper, normalize):
     """Appendix A, equation (4): the product of layer l multiplied by gamma_l in the forward pass, hence in
     both gradients.  With the standardisation the factor of a hidden layer only matters through epsilon."""
