@@ -214,10 +214,11 @@ __global__ __launch_bounds__(kThreads) void k_wide_out_stats(WideOutArgs a)
 // later: dW and the updated weights.  The workgroup's share of dh stays in registers over all its tiles, 32 samples
 // x 128 hidden neurons per wave: a wave of group 0 adds the tile's term for the first 32 of its 64 samples right after
 // writing their dz, its partner in group 1 the term for the other 32 one slot later (with all of dh in group 1 that
-// group's chain of dependent LDS reads and MFMAs set the pace).  One workgroup barrier per slot; dz and the outgoing weights alternate between two buffers, the W tiles
-// between three (tile s is read by group 0, tile s - 1 by group 1, tile s + 1 arrives).
+// group's chain of dependent LDS reads and MFMAs set the pace).  One workgroup barrier per slot; dz and the outgoing
+// weights alternate between two buffers, the W tiles between three (tile s is read by group 0, tile s - 1 by
+// group 1, tile s + 1 arrives).
 constexpr int kC2 = 32;          // classes per tile
-constexpr int kDepth = 2;        // W tiles requested ahead (16 bytes per lane each; 3 would spill registers)
+constexpr int kDepth = 2;        // W tiles requested ahead (16 bytes per lane each; 3 and 4 measured no faster)
 
 struct SmemBackward {
     uint16_t H[kB * kK];          // h_{t-1} of the subnet          [sample][hidden]
