@@ -237,8 +237,8 @@ ist_status ist_create(const ist_model_desc *d, int32_t max_B, ist_ctx **out)
     ctx->off_zeros = w; w = align_up(w + 256);   // stays zero: source of out-of-range operand chunks
     ctx->off_rowloss = w; w = align_up(w + sizeof(float) * (size_t)kLossSlots * S * max_B);
     ctx->off_bitmap = w;
-    if (d->input == IST_CSR)
-        w = align_up(w + sizeof(uint32_t) * (size_t)S * ctx->dims[0] * ((max_B + 31) / 32));
+    if (d->input == IST_CSR)   // per (subnet, input column): one bit per sample, then one 64-bit "first occurrence" word
+        w = align_up(w + csr_scratch_bytes(S, ctx->dims[0], max_B));
     ctx->off_err = w; w = align_up(w + sizeof(int32_t));
     // split-K scratch: the largest partial buffer any forward / backward-data product needs
     size_t pmax = 0;

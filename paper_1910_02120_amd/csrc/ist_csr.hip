@@ -64,8 +64,27 @@ hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t st)
     return launch_fill_u32(p, (int64_t)(bytes / 4), 0u, st);
 }
 
-// bitmap[g][col][b >> 5] |= 1 << (b & 31) for every non-zero (b, col) of group g
-__global__ __launch_bounds__(256) void k_csr_mark(CsrArgs c, uint32_t *__restrict__ bitmap, int words)
+// Scratch of the sparse update, per (group, column): `words` bitmap words (one bit per sample), and after all of
+// them one 64-bit word per pair that names the column's first occurrence in the batch.
+__host__ __device__ inline int64_t csr_bitmap_words(int64_t G, int64_t N0, int words) { return (G * N0 * words + 1) / 2 * 2; }
+size_t csr_scratch_bytes(int64_t G, int64_t N0, int64_t B)
+{
+    return (size_t)csr_bitmap_words(G, N0, (int)((B + 31) / 32)) * 4 + (size_t)G * N0 * 8;
+}
+constexpr uint64_t kPosMask = (1ull << 40) - 1;   // first[] = ((sample << 40) | position in vals) + 1; 0: look it up
+
+__global__ void k_csr_clear(uint32_t *bitmap, int64_t nwords, uint64_t *first, int64_t npairs)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += stride) bitmap[i] = 0u;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < npairs; i += stride) first[i] = ~0ull;
+}
+
+// bitmap[g][col][b >> 5] |= 1 << (b & 31) for every non-zero (b, col) of group g; first[g][col] = the smallest
+// (sample, position) + 1 among them - for a column that a single sample holds that is where its value lies, and
+// the update needs no search - or 0 where a sample's row repeats the column (the values then have to be added up)
+__global__ __launch_bounds__(256) void k_csr_mark(CsrArgs c, uint32_t *__restrict__ bitmap, unsigned long long *__restrict__ first,
+                                                  int words)
 {
     const int g = blockIdx.y, b = blockIdx.x;
     const int64_t row = c.row0 + (int64_t)g * c.stride_g + b;
@@ -75,7 +94,11 @@ __global__ __launch_bounds__(256) void k_csr_mark(CsrArgs c, uint32_t *__restric
     for (int64_t p = p0 + threadIdx.x; p < p1; p += blockDim.x) {
         int32_t col = c.colidx[p];
         if (col < 0 || col >= c.N0) continue;
-        atomicOr(bitmap + ((int64_t)g * c.N0 + col) * words + (b >> 5), 1u << (b & 31));
+        const int64_t pair = (int64_t)g * c.N0 + col;
+        const uint32_t bit = 1u << (b & 31);
+        const uint32_t old = atomicOr(bitmap + pair * words + (b >> 5), bit);
+        const bool simple = !(old & bit) && (uint64_t)p < kPosMask;
+        atomicMin(first + pair, simple ? (((unsigned long long)b << 40) | (unsigned long long)p) + 1ull : 0ull);
     }
 }
 
@@ -90,8 +113,8 @@ constexpr int kFewSamples = 2;   // (1, 2, 4 measured alike: 180 us per step on 
 template <typename D>
 __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__restrict__ Wt,
                                                     const typename D::T *__restrict__ dz,
-                                                    const uint32_t *__restrict__ bitmap, int words,
-                                                    float lr)
+                                                    const uint32_t *__restrict__ bitmap,
+                                                    const uint64_t *__restrict__ first, int words, float lr)
 {
     using T = typename D::T;
     const int lane = threadIdx.x & 63;
@@ -100,21 +123,35 @@ __global__ __launch_bounds__(256) void k_csr_update(CsrArgs c, typename D::T *__
     const int64_t w0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
     const int64_t total = (int64_t)c.G * c.N0;
     if (w0 >= total) return;
-    bool mine = false;
+    int holders = 0;          // samples that hold this lane's column
+    uint64_t where = 0;       // and, if it is one, where its value lies
     if (w0 + lane < total) {
         const uint32_t *b0 = bitmap + (w0 + lane) * words;
-        for (int i = 0; i < words; ++i) mine |= (b0[i] != 0u);
+        for (int i = 0; i < words; ++i) holders += __popc(b0[i]);
+        where = first[w0 + lane];
     }
-    unsigned long long present = __ballot(mine);
+    unsigned long long present = __ballot(holders != 0);
     const T *vals = static_cast<const T *>(c.vals);
     while (present) {
-        const int64_t wid = w0 + (__ffsll((long long)present) - 1);
+        const int idx = __ffsll((long long)present) - 1;
+        const int64_t wid = w0 + idx;
         present &= present - 1;
         const int g = (int)(wid / c.N0);
         const int32_t col = (int32_t)(wid % c.N0);
         const uint32_t *bm = bitmap + wid * words;
         T *wrow = Wt + ((int64_t)g * c.N0 + col) * c.w;
         const T *dzg = dz + (int64_t)g * c.B * c.ld;
+        const int n_hold = __shfl(holders, idx);
+        const uint64_t wh = ((uint64_t)(uint32_t)__shfl((int)(where >> 32), idx) << 32) | (uint32_t)__shfl((int)(uint32_t)where, idx);
+        if (n_hold == 1 && wh != 0ull) {
+            // one sample, one entry: value, dz row and old weights in a single round trip
+            const int b = (int)((wh - 1) >> 40);
+            const float xv = D::up(vals[(wh - 1) & kPosMask]);
+            const T *dr = dzg + (int64_t)b * c.ld;
+            for (int64_t q = lane; q < c.w; q += 64)
+                wrow[q] = D::cvt(D::up(wrow[q]) - lr * (xv * D::ld(dr + q)));
+            continue;
+        }
         for (int64_t q0 = 0; q0 < c.w; q0 += 256) {          // 4 outputs per lane per pass
             float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
             float wold[4];
@@ -217,18 +254,19 @@ hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_
                              int dtype, hipStream_t st)
 {
     const int words = (c.B + 31) / 32;
-    const int64_t nwords = (int64_t)c.G * c.N0 * words;
-    hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, st, bitmap, nwords, 0u);
+    const int64_t npairs = (int64_t)c.G * c.N0;
+    uint64_t *first = reinterpret_cast<uint64_t *>(bitmap + csr_bitmap_words(c.G, c.N0, words));
+    hipLaunchKernelGGL(k_csr_clear, dim3(2048), dim3(256), 0, st, bitmap, npairs * words, first, npairs);
     hipLaunchKernelGGL(k_csr_mark, dim3((unsigned)c.B, (unsigned)c.G), dim3(256), 0, st, c, bitmap,
-                       words);
-    const int64_t waves = ((int64_t)c.G * c.N0 + 63) / 64;   // 64 (group, column) pairs per wavefront
+                       reinterpret_cast<unsigned long long *>(first), words);
+    const int64_t waves = (npairs + 63) / 64;   // 64 (group, column) pairs per wavefront
     dim3 grid((unsigned)((waves + 3) / 4));
     if (dtype == IST_BF16)
         hipLaunchKernelGGL(k_csr_update<BF16>, grid, dim3(256), 0, st, c, (uint16_t *)Wt,
-                           (const uint16_t *)dz, bitmap, words, lr);
+                           (const uint16_t *)dz, bitmap, first, words, lr);
     else
         hipLaunchKernelGGL(k_csr_update<F32>, grid, dim3(256), 0, st, c, (float *)Wt,
-                           (const float *)dz, bitmap, words, lr);
+                           (const float *)dz, bitmap, first, words, lr);
     return hipGetLastError();
 }
 

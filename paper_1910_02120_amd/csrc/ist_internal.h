@@ -294,6 +294,8 @@ hipError_t launch_fill_u32(void *p, int64_t n, uint32_t v, hipStream_t st);
 // rowmajor: Wt is W_1 itself, [w][N0] (full-network evaluation), not the transposed subnet block
 hipError_t launch_csr_forward(const CsrArgs &c, const void *Wt, const void *bias, void *h, float *z_out,
                               int dtype, hipStream_t st, bool rowmajor = false);
+// bitmap: scratch of csr_scratch_bytes(G, N0, B) bytes, 8-byte aligned (cleared by the call itself)
+size_t csr_scratch_bytes(int64_t G, int64_t N0, int64_t B);
 hipError_t launch_csr_update(const CsrArgs &c, void *Wt, const void *dz, uint32_t *bitmap,
                              float lr, int dtype, hipStream_t st);
 
