@@ -311,6 +311,52 @@ def test_csr_with_empty_rows_and_unused_columns():
     ctx.close()
 
 
+@pytest.mark.parametrize("name", ["csr-f32", "csr-bf16-even", "cfg5-small"])
+def test_csr_rows_that_repeat_a_column(name):
+    """A sample's column list may name a column more than once: its values are summed, on both sides.  Every
+    third row gets its second entry's column replaced by the first's (the lists stay ascending), so columns
+    held by one sample, by several, and repeated inside a row all occur."""
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, dev=_dev())
+    changed = 0
+    for r in range(0, len(P.rp) - 1, 3):
+        p0, p1 = int(P.rp[r]), int(P.rp[r + 1])
+        if p1 - p0 >= 2:
+            P.ci[p0 + 1] = P.ci[p0]
+            changed += 1
+    assert changed > 10
+    P.upload()
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    _, _, _, worst = H.check_training(P, ctx)
+    print(f"{name} with {changed} repeated columns: worst parameter rel err {worst:.3e} (tol {H.TOL[cfg.dtype]})")
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["cfg3-small", "cfg5-small", "wide-update-bf16"])
+def test_zero_learning_rate_changes_nothing(name):
+    """lr = 0: every parameter keeps its bits (the update kernels that fold the old weights into their
+    accumulators divide by lr and must step aside)."""
+    cfg = SHAPES[name]
+    P = H.Problem(cfg, dev=_dev())
+    ctx = P.context()
+    ctx.partition(P.dW, P.db, P.dperm)
+    before = [[(H.bits(W).copy(), H.bits(b).copy()) for W, b in (ctx.subnet_export(s, l) for l in range(1, cfg.t + 1))]
+              for s in range(cfg.S)]
+    lo = torch.zeros(cfg.S * 2, dtype=torch.float32, device=P.dev)
+    csr = None if P.dcsr is None else P.dcsr
+    ctx.subnet_steps(P.dy, 0.0, 2, cfg.B, X=None if P.dX is None else P.dX.reshape(-1, cfg.dims[0]), csr=csr,
+                     stride_s=cfg.k * cfg.B, stride_k=cfg.B, loss_out=lo)
+    torch.cuda.synchronize()
+    assert np.isfinite(lo.cpu().numpy()).all()
+    for s in range(cfg.S):
+        for l in range(1, cfg.t + 1):
+            W, b = ctx.subnet_export(s, l)
+            assert np.array_equal(H.bits(W), before[s][l - 1][0]), (s, l, "W")
+            assert np.array_equal(H.bits(b), before[s][l - 1][1]), (s, l, "b")
+    ctx.close()
+
+
 @pytest.mark.parametrize("dims,S,B", [((12, 16, 1), 4, 6), ((20, 64, 64, 3), 64, 5)])
 def test_single_class_and_as_many_subnets_as_neurons(dims, S, B):
     cfg = _mk(f"edge-{dims[-1]}-{S}", "cfg2", dims=dims, S=S, B=B, k=2, lr=0.05)
