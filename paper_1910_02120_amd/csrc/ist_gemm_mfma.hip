@@ -266,14 +266,6 @@ __device__ inline void epi8(const GemmArgs &a, int g, int gz, int m, int n0, flo
         }
         return;
     }
-    if (EPI == EPI_UPDATE_ACC) {
-        // the accumulators started at -w / lr: w - lr dW = 0 - lr acc (the subtraction from +0 keeps a zero weight
-        // with a zero gradient at +0); chunks are whole here (the launcher takes this path for N % 8 == 0 only)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) val[i] = 0.0f - a.lr * val[i];
-        Row8<T>::st(static_cast<T *>(a.C) + ci, vec, nv, val);
-        return;
-    }
     float o[8];
     if (EPI == EPI_BWD_DATA) {
         if (HASPRE && vec) pre8_decode<T>(pre, o);
@@ -787,6 +779,37 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
         // the LDS executes a wave's accesses in order, no workgroup barrier is needed in here.
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            if constexpr (ACCW) {
+                // The accumulators hold -w / lr + dW: the new weights w - lr dW = 0 - lr * acc (the subtraction from +0
+                // keeps a zero weight with a zero gradient at +0) are final before they are staged, so
+                // they go through the staging rows as bf16 (half the LDS traffic; row pitch 72 elements keeps the
+                // 16-byte reads aligned) and leave as the 16-byte pieces read back.  Whole pieces only (N % 8 == 0).
+                constexpr int LDH = 32 * TN + 8;
+                uint16_t *st16 = reinterpret_cast<uint16_t *>(stage);
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint2 o;
+                        o.x = f32x2_to_bf16x2(0.0f - a.lr * acc[i][j][4 * q], 0.0f - a.lr * acc[i][j][4 * q + 1]);
+                        o.y = f32x2_to_bf16x2(0.0f - a.lr * acc[i][j][4 * q + 2], 0.0f - a.lr * acc[i][j][4 * q + 3]);
+                        *reinterpret_cast<uint2 *>(st16 + (lane & 31) * LDH + 32 * j + 8 * q + 4 * (lane >> 5)) = o;
+                    }
+                // the next tile's weights, slice by slice as the accumulators of this tile's slices retire (a last
+                // tile asks for its own weights again and drops them)
+                preload(i, pre[i], g, m0, n0);
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int p = 0; p < 32 / RPP; ++p) {
+                    const int row = p * RPP + lane / CPR, ch = lane % CPR;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(st16 + row * LDH + 8 * ch);
+                    const int m = cm0 + wm + i * 32 + row, n = cn0 + wn + 8 * ch;
+                    if (m < a.M && n < a.N)
+                        *reinterpret_cast<uint4 *>(static_cast<T *>(a.C) + (int64_t)cg * a.gC + (int64_t)m * a.ldc + n) = v;
+                }
+                continue;
+            }
             __builtin_amdgcn_wave_barrier();
             if (kg == 0) {
 #pragma unroll
@@ -818,14 +841,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
                             if (ch == 0 && m < a.M && blk < a.nb) a.pmax[((int64_t)cg * a.nb + blk) * a.M + m] = s;
                         }
                     } else
-                        epi8<D, EPI, PRE && !ACCW>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
-                                                   val, vecC, bias8, ACCW ? Pre8<T>{} : pre[i % PD][p]);
+                        epi8<D, EPI, PRE>(a, cg, EPI == EPI_PARTIAL ? cgz : cg, cm0 + wm + i * 32 + row, cn0 + wn + 8 * ch,
+                                          val, vecC, bias8, pre[i % PD][p]);
                 }
             }
             if (PRE && !ACCW && i + PD < TM) preload(i + PD, pre[i % PD], cg, cm0, cn0);
-            // the next tile's weights, slice by slice as the accumulators of this tile's slices retire (a last tile
-            // asks for its own weights again and drops them)
-            if constexpr (ACCW) preload(i, pre[i], g, m0, n0);
         }
         }
         if (!more) break;
