@@ -37,8 +37,6 @@
 
 namespace ist {
 
-
-
 template <typename D, int KT> struct Mma;   // KT: k extent of one LDS tile
 
 template <int KT> struct Mma<BF16, KT> {
@@ -319,7 +317,7 @@ template <int A, int B> struct MaxOf { static constexpr int v = A > B ? A : B; }
 template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN, int KG, int ST, bool VEC, int KT,
           bool PERSIST, bool DB, bool SLICE>
 __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int splits, int k_per_split, int tiles_x,
-                                          int tiles_y, int stagger, int stagger_sleeps, int bid_, int nblk_)
+                                          int tiles_y, int stagger, int stagger_sleeps, int bid_, int nblk_, int xcd)
 {
     // a plain launch reads its position from the hardware registers (passing them through arguments was seen to
     // cost registers: a kernel at its limit started to spill)
@@ -352,9 +350,20 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
     // Block tiles are numbered n-fastest, then m, then (group, split); a workgroup takes
     // tiles t = bid, bid + nblk, ... and issues the first loads of its
     // next tile before the epilogue of the current one.
+    // xcd != 0 (the launcher sets it only when 8 divides both the tile count and the grid): workgroups are handed
+    // to the 8 XCDs round-robin by their index and each XCD has an L2 of its own, so the workgroups with
+    // bid % 8 == x together walk one contiguous eighth of the tile list (with 8 subnets: one subnet's operands per
+    // L2 instead of all of them in every L2), and within a group's tile grid the list runs down 8 rows of tiles before
+    // it moves one tile to the right, so that the tiles in flight on an XCD share few operand panels.
     const int per_z = tiles_x * tiles_y;
     const int total = per_z * a.G * splits;
-    int t = bid;
+    int t = bid, t_step = nblk, t_end = total;
+    if (xcd) {
+        const int chunk = total >> 3;
+        t_step = nblk >> 3;
+        t = (bid & 7) * chunk + (bid >> 3);
+        t_end = ((bid & 7) + 1) * chunk;
+    }
     int g, gz, m0, n0, kbeg, kend;
     const E *A, *B;
     auto decode = [&](int tt) {
@@ -362,8 +371,15 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
         const int r = tt - gz * per_z;
         g = gz / splits;
         const int sp = gz - g * splits;
-        m0 = (r / tiles_x) * BM;
-        n0 = (r % tiles_x) * BN;
+        if (xcd) {
+            const int band = 8 * tiles_x, bi = r / band, q = r - bi * band;
+            const int rows = min(tiles_y - 8 * bi, 8);
+            m0 = (8 * bi + q % rows) * BM;
+            n0 = (q / rows) * BN;
+        } else {
+            m0 = (r / tiles_x) * BM;
+            n0 = (r % tiles_x) * BN;
+        }
         kbeg = sp * k_per_split;
         kend = min(a.K, kbeg + k_per_split);
         A = static_cast<const E *>(a.A) + (int64_t)g * a.gA;
@@ -655,8 +671,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs &a, bool vecC, int spli
         // ---- first loads of the next tile, so that they fly during this epilogue ----
         // (only where workgroups walk several tiles: the extra live state costs registers)
         const int cg = g, cgz = gz, cm0 = m0, cn0 = n0;
-        const int tn = t + nblk;
-        const bool more = PERSIST && tn < total;
+        const int tn = t + t_step;
+        const bool more = PERSIST && tn < t_end;
         if (PERSIST) {
             decode(more ? tn : t);   // unconditional (a last tile re-reads its own first k-tile):
             prologue();              // a branch around loads would force the loop to drain them
@@ -865,10 +881,10 @@ template <typename D, bool AK, bool BKC, int EPI, int BM, int BN, int WM, int WN
           bool PERSIST = (EPI == EPI_UPDATE), bool DB = false>
 __global__ IST_GEMM_BOUNDS
 void k_gemm_mfma(GemmArgs a, bool vecC, int splits, int k_per_split, int tiles_x, int tiles_y, int stagger,
-                 int stagger_sleeps)
+                 int stagger_sleeps, int xcd)
 {
     gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB, false>(
-        a, vecC, splits, k_per_split, tiles_x, tiles_y, stagger, stagger_sleeps, 0, 0);
+        a, vecC, splits, k_per_split, tiles_x, tiles_y, stagger, stagger_sleeps, 0, 0, xcd);
 }
 
 // Several independent products of one shape class in one launch (the weight updates of all layers of a
@@ -902,7 +918,7 @@ void k_gemm_mfma_multi(GemmMulti mm)
     gemm_body<D, AK, BKC, EPI, BM, BN, WM, WN, KG, ST, VEC, KT, PERSIST, DB, true>(a, mm.vecC[i] != 0, 1, a.K, mm.tiles_x[i],
                                                                                     mm.tiles_y[i], 0, 0,
                                                                                     (int)blockIdx.x - mm.first[i],
-                                                                                    mm.first[i + 1] - mm.first[i]);
+                                                                                    mm.first[i + 1] - mm.first[i], 0);
 }
 
 // out[g][m][n] = epilogue(sum_sp partial[g*splits + sp][m][n]) for split-K launches.
@@ -1043,16 +1059,19 @@ static double algo_bytes(const GemmArgs &a, int epi, int esz)
 template <int BM, int BN, typename K>
 static void launch_tiles(K kernel, int threads, const GemmArgs &a, bool vecC, int splits, int kps, hipStream_t st,
                          bool persist = false, int64_t cap = 256 * 3 * 4 /* 256 CUs x 3 resident workgroups x 4 */,
-                         int stagger = 0, int stagger_sleeps = 0)
+                         int stagger = 0, int stagger_sleeps = 0, bool xcd_order = false)
 {
     const int tx = (a.N + BN - 1) / BN, ty = (a.M + BM - 1) / BM;
     const int64_t total = (int64_t)tx * ty * a.G * splits;
     const unsigned grid = (unsigned)(persist && total >= 4 * cap ? cap : total);
+    // the per-XCD tile order needs equal shares: 8 divides the tile count and the grid (then every workgroup
+    // has at least one tile of its XCD's share, since grid <= total)
+    const int xcd = (xcd_order && total % 8 == 0 && grid % 8 == 0) ? 1 : 0;
     char label[64];
     snprintf(label, sizeof(label), "gemm_%s_%dx%d_t%d%s%s", s_label, BM, BN, threads, persist ? "_persistent" : "",
              splits > 1 ? "_splitk" : "");
     tag_kernel(label, 2.0 * a.M * a.N * (double)a.K * a.G, s_bytes);
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty, stagger, stagger_sleeps);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, a, vecC, splits, kps, tx, ty, stagger, stagger_sleeps, xcd);
 }
 
 template <typename D, bool AK, bool BKC, int EPI, bool VEC>
@@ -1113,7 +1132,7 @@ static hipError_t launch_vec(const GemmArgs &a, hipStream_t st)
             if (a.K > 256 && a.M > 128 && a.N >= 256 &&
                 (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256) * a.G >= 256) {
                 launch_tiles<256, 256>(k_gemm_mfma<D, AK, BKC, EPI, 256, 256, 2, 4, 1, 1, VEC, 64, false, true>, 512, a, vecC,
-                                       1, a.K, st, false);
+                                       1, a.K, st, false, 256 * 3 * 4, 0, 0, true);
                 done = true;
             }
         }
