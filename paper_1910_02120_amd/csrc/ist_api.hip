@@ -444,19 +444,26 @@ static ist_status build_tables(ist_ctx *ctx, char *base, const int32_t *const *p
             IST_HIP(launch_fill_u32(ctx->workspace + ctx->hidden[l - 1].off_invpos, ctx->hidden[l - 1].N, 0xffffffffu, st),
                     "clear invpos");
     }
-    for (int l = 1; l < t; ++l) {
-        const HiddenPlan &h = ctx->hidden[l - 1];
-        int32_t *invpos = reinterpret_cast<int32_t *>(ctx->workspace + h.off_invpos);
-        IST_RUN(KC_PERM_TABLES, launch_perm_tables(perm[l - 1], h.N, S, invpos,
-                                   reinterpret_cast<int32_t *>(base + h.off_sorted),
-                                   reinterpret_cast<int32_t *>(base + h.off_slot),
-                                   reinterpret_cast<int32_t *>(base + h.off_p2q),
-                                   reinterpret_cast<uint32_t *>(base + h.off_mask),
-                                   reinterpret_cast<int32_t *>(base + h.off_rank),
-                                   ctx->errflag(), st), "perm tables");
-        if (ctx->checked)
-            IST_RUN(KC_PERM_TABLES, launch_perm_check(perm[l - 1], invpos, h.N, ctx->errflag(), st), "perm check");
+    for (int l0 = 1; l0 < t; l0 += kMaxPermJobs) {   // all hidden layers (8 at a time) in two launches
+        PermJobs pj{};
+        pj.S = S;
+        for (int l = l0; l < t && l < l0 + kMaxPermJobs; ++l) {
+            const HiddenPlan &h = ctx->hidden[l - 1];
+            pj.job[pj.njobs++] = PermJob{perm[l - 1], reinterpret_cast<int32_t *>(ctx->workspace + h.off_invpos),
+                                         reinterpret_cast<int32_t *>(base + h.off_sorted),
+                                         reinterpret_cast<int32_t *>(base + h.off_slot),
+                                         reinterpret_cast<int32_t *>(base + h.off_p2q),
+                                         reinterpret_cast<uint32_t *>(base + h.off_mask),
+                                         reinterpret_cast<int32_t *>(base + h.off_rank), h.N};
+        }
+        IST_RUN(KC_PERM_TABLES, launch_perm_tables(pj, ctx->errflag(), st), "perm tables");
     }
+    if (ctx->checked)
+        for (int l = 1; l < t; ++l) {
+            const HiddenPlan &h = ctx->hidden[l - 1];
+            IST_RUN(KC_PERM_TABLES, launch_perm_check(perm[l - 1], reinterpret_cast<const int32_t *>(ctx->workspace + h.off_invpos),
+                                                      h.N, ctx->errflag(), st), "perm check");
+        }
     if (ctx->checked) {
         int32_t flag = 0;
         IST_HIP(hipMemcpyAsync(&flag, ctx->errflag(), sizeof(flag), hipMemcpyDeviceToHost, st), "read flag");

@@ -124,9 +124,16 @@ extern thread_local KernelTag g_tag;
 void tag_kernel(const char *label, double flops, double bytes);
 
 // ----------------------------------------------------------------- partition / merge
-hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
-                              int32_t *sorted, int32_t *slot, int32_t *p2q, uint32_t *mask,
-                              int32_t *rank, int32_t *err, hipStream_t st);
+// Block tables of several hidden layers (N neurons each, S blocks) from their permutations, two launches for
+// all of them: invpos = inverse permutation (scratch), then per block the neuron ids sorted ascending (sorted),
+// each neuron's packed position (slot), packed position by permutation position (p2q), membership bitmask per
+// block (mask) and the count of members before each 32-neuron word (rank).  Fills in the blk0 fields itself.
+constexpr int kMaxPermJobs = 8;
+struct PermJob {
+    const int32_t *perm; int32_t *invpos, *sorted, *slot, *p2q; uint32_t *mask; int32_t *rank; int64_t N;
+};
+struct PermJobs { PermJob job[kMaxPermJobs]; int32_t inv_blk0[kMaxPermJobs + 1], sort_blk0[kMaxPermJobs + 1]; int32_t njobs, S; };
+hipError_t launch_perm_tables(PermJobs &jobs, int32_t *err, hipStream_t st);
 
 // out[g][i][j] = W[rows ? rows[g*nr+i] : i][cols ? cols[g*nc+j] : j]  (or the
 // reverse copy when scatter is set); transposed: the subnet block is [nc][nr].

@@ -21,14 +21,24 @@ __device__ inline uint4 ld_stream(const uint4 *p)
 // ----------------------------------------------------------------------------
 // index tables
 // ----------------------------------------------------------------------------
-__global__ void k_perm_invert(const int32_t *__restrict__ perm, int64_t N,
-                              int32_t *__restrict__ invpos, int32_t *err)
+// The tables of up to kMaxPermJobs hidden layers are built by one launch of each of the two kernels: workgroup
+// b works on the layer i with blk0[i] <= b < blk0[i + 1].
+__device__ inline int perm_job_of(const int32_t *blk0, int njobs, int b)
 {
-    int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= N) return;
-    int32_t c = perm[p];
-    if (c < 0 || c >= N) { atomicOr(err, 1); return; }
-    invpos[c] = (int32_t)p;
+    int i = 0;
+    while (i + 1 < njobs && b >= blk0[i + 1]) ++i;
+    return i;
+}
+
+__global__ void k_perm_invert(PermJobs jobs, int32_t *err)
+{
+    const int i = perm_job_of(jobs.inv_blk0, jobs.njobs, (int)blockIdx.x);
+    const PermJob &j = jobs.job[i];
+    int64_t p = (int64_t)((int)blockIdx.x - jobs.inv_blk0[i]) * blockDim.x + threadIdx.x;
+    if (p >= j.N) return;
+    int32_t c = j.perm[p];
+    if (c < 0 || c >= j.N) { atomicOr(err, 1); return; }
+    j.invpos[c] = (int32_t)p;
 }
 
 __global__ void k_perm_check(const int32_t *__restrict__ perm, const int32_t *__restrict__ invpos,
@@ -45,23 +55,29 @@ __global__ void k_perm_check(const int32_t *__restrict__ perm, const int32_t *__
 // all smaller ids (coalesced reads of the 4-byte table, no barrier inside the loop), which gives
 // the packed position of its first member without any dependence on other workgroups.
 constexpr int kSortThreads = 1024;
-__global__ __launch_bounds__(kSortThreads) void k_perm_sort(
-    const int32_t *__restrict__ invpos, int64_t N, int64_t w, int32_t S, int32_t *__restrict__ sorted,
-    int32_t *__restrict__ slot, int32_t *__restrict__ p2q, uint32_t *__restrict__ mask,
-    int32_t *__restrict__ rank, int64_t words)
+__global__ __launch_bounds__(kSortThreads) void k_perm_sort(PermJobs jobs)
 {
     __shared__ int32_t wave_cnt[kSortThreads / 64];
     __shared__ int32_t wave_pre[kSortThreads / 64];
+    const int ji = perm_job_of(jobs.sort_blk0, jobs.njobs, (int)blockIdx.x);
+    const PermJob &job = jobs.job[ji];
+    const int32_t *__restrict__ invpos = job.invpos;
+    int32_t *__restrict__ sorted = job.sorted, *__restrict__ slot = job.slot, *__restrict__ p2q = job.p2q;
+    uint32_t *__restrict__ mask = job.mask;
+    int32_t *__restrict__ rank = job.rank;
+    const int32_t S = jobs.S;
+    const int64_t N = job.N, w = (N + S - 1) / S, words = (N + 31) / 32;
+    const int chunk = (int)blockIdx.x - jobs.sort_blk0[ji];
     const int s = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t c0 = (int64_t)blockIdx.x * kSortThreads;
+    const int64_t c0 = (int64_t)chunk * kSortThreads;
     // subnet s owns the permutation positions [p_lo, p_hi): N = q S + r, the first r blocks one wider;
     // its packed positions are s * w + 0 .. w - 1 (w = ceil(N / S)), the last one empty in a narrower block
     const int64_t qn = N / S, rn = N % S;
     const int64_t ws = qn + (s < rn ? 1 : 0);
     const int64_t p_lo = (int64_t)s * qn + (s < rn ? s : rn), p_hi = p_lo + ws;
     const int64_t pack0 = (int64_t)s * w;
-    if (blockIdx.x == 0)
+    if (chunk == 0)
         for (int64_t q = ws + threadIdx.x; q < w; q += kSortThreads) sorted[pack0 + q] = -1;
     int cnt = 0;
     for (int64_t c = threadIdx.x; c < c0; c += kSortThreads) {
@@ -102,15 +118,22 @@ __global__ __launch_bounds__(kSortThreads) void k_perm_sort(
     }
 }
 
-hipError_t launch_perm_tables(const int32_t *perm, int64_t N, int32_t S, int32_t *invpos,
-                              int32_t *sorted, int32_t *slot, int32_t *p2q, uint32_t *mask,
-                              int32_t *rank, int32_t *err, hipStream_t st)
+hipError_t launch_perm_tables(PermJobs &jobs, int32_t *err, hipStream_t st)
 {
     const int th = 256;
-    const unsigned nb = (unsigned)((N + th - 1) / th);
-    hipLaunchKernelGGL(k_perm_invert, dim3(nb), dim3(th), 0, st, perm, N, invpos, err);
-    hipLaunchKernelGGL(k_perm_sort, dim3((unsigned)((N + kSortThreads - 1) / kSortThreads), (unsigned)S),
-                       dim3(kSortThreads), 0, st, invpos, N, (N + S - 1) / S, S, sorted, slot, p2q, mask, rank, (N + 31) / 32);
+    if (jobs.njobs < 1 || jobs.njobs > kMaxPermJobs) return hipErrorInvalidValue;
+    int64_t nb = 0, ns = 0;
+    for (int i = 0; i < jobs.njobs; ++i) {
+        jobs.inv_blk0[i] = (int32_t)nb;
+        jobs.sort_blk0[i] = (int32_t)ns;
+        nb += (jobs.job[i].N + th - 1) / th;
+        ns += (jobs.job[i].N + kSortThreads - 1) / kSortThreads;
+    }
+    if (nb > 0x7fffffffLL) return hipErrorInvalidValue;
+    jobs.inv_blk0[jobs.njobs] = (int32_t)nb;
+    jobs.sort_blk0[jobs.njobs] = (int32_t)ns;
+    hipLaunchKernelGGL(k_perm_invert, dim3((unsigned)nb), dim3(th), 0, st, jobs, err);
+    hipLaunchKernelGGL(k_perm_sort, dim3((unsigned)ns, (unsigned)jobs.S), dim3(kSortThreads), 0, st, jobs);
     return hipGetLastError();
 }
 
