@@ -55,6 +55,10 @@ SHAPES = {
     # wide output layer with a full 256-row batch: the row-statistics pass takes its 256x256 blocks
     "wide-out-bf16-B256": _mk("wide-out-bf16-B256", "cfg5", dims=(200, 512, 33001), S=8, B=256, k=2,
                               nnz_per_row=10, lr=0.5),
+    # a wide bf16 output layer behind more than 128 hidden neurons per subnet: both cross-entropy passes recompute
+    # the logits with 256 x 256 blocks (264 = 256 + 8 hidden neurons per subnet, 10500 = 41 x 256 + 4 classes: the
+    # transposed dz pass walks a grid of 42 x 1 blocks per subnet, five bands of 8 block rows and one of 2)
+    "wide-out-gemm-bf16": _mk("wide-out-gemm-bf16", "cfg3", dims=(100, 2112, 10500), S=8, B=256, k=2, lr=0.5),
     # more layers than one bias launch, one bias-copy launch or one shared update launch takes (16 / 16 / 4);
     # initial weights 1.5 x Xavier so that the gradient survives the 18 ReLU layers down to the first
     "very-deep-f32": _mk("very-deep-f32", "cfg2", dims=(16,) + (32,) * 18 + (5,), S=2, B=6, k=2, lr=0.05,
