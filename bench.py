@@ -44,12 +44,12 @@ MEASURED_TRAFFIC = {
     # read 77.05 MB (FETCH_SIZE 37623.1 KiB x 2.000) + written 34.16 MB (WRITE_SIZE 33360.7 KiB x 1.000)
     "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3_bias": 111.21e6},
     "cfg4": {
-        # read 1707.7 MB (833881.1 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000), average of the three layers
-        "gemm_update_bf16_256x256_t512_persistent": 2602.5e6,
-        # read 1381.1 MB + written 67.1 MB
-        "gemm_fwd_relu_bf16_256x256_t512": 1448.2e6,
-        # read 1678.0 MB + written 67.1 MB
-        "gemm_bwd_data_bf16_256x256_t512": 1745.2e6,
+        # read 1797.7 MB (877819.1 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000), average of the three layers
+        "gemm_update_bf16_256x256_t512_persistent": 2692.5e6,
+        # read 1007.8 MB + written 67.1 MB (every operand byte fetched once: tiles are ordered by XCD)
+        "gemm_fwd_relu_bf16_256x256_t512": 1074.9e6,
+        # read 1275.4 MB + written 67.1 MB
+        "gemm_bwd_data_bf16_256x256_t512": 1342.5e6,
     },
     "cfg5": {
         # backward launch of the wide output layer: read 1407.7 MB (687385.7 KiB x 2.000) + written 1421.3 MB
