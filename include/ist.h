@@ -158,7 +158,9 @@ ist_status ist_merge(ist_ctx *ctx, const ist_params *params, void *stream);
  * writes is the row partition would read back.  The new blocks are built in a second
  * subnet buffer given once with ist_bind_spare (same size and alignment as `subnets` of
  * ist_bind, caller-owned device memory, must stay valid while the context is used); the
- * two buffers change roles at every call; ist_bind forgets the spare (give it again after a
+ * two buffers change roles at every call (on the host: a HIP graph recorded from this call
+ * keeps the roles it saw and must not be replayed; ist_partition, ist_subnet_steps and ist_merge
+ * have no such state and may be); ist_bind forgets the spare (give it again after a
  * re-bind).  IST_ESTATE before ist_partition or without a
  * spare buffer; with checking on, a perm that is not a permutation gives IST_EPERM and
  * leaves `params` and the current subnets untouched.
