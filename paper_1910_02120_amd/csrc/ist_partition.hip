@@ -232,12 +232,21 @@ constexpr int kTrQ = 64, kTrC = 128;
 template <bool SCATTER>
 __global__ __launch_bounds__(256) void k_rows_transposed16(uint16_t *__restrict__ W, int64_t ld,
                                                            uint16_t *__restrict__ sub, const int32_t *__restrict__ rows,
-                                                           int64_t nr, int64_t nc)
+                                                           int64_t nr, int64_t nc, int64_t ncx, int64_t nqy, int32_t G)
 {
     __shared__ uint32_t tile[kTrQ][kTrC / 2 + 2];
     __shared__ int64_t start[kTrQ];                         // element index of (row, c0) in W
-    const int g = blockIdx.z;
-    const int64_t q0 = (int64_t)blockIdx.y * kTrQ, c0 = (int64_t)blockIdx.x * kTrC;
+    // Tiles are numbered column tile fastest, then row tile, then subnet (ncx * nqy * G of them), and the 8 XCDs
+    // (workgroup index mod 8) each take one contiguous eighth of that list: a row piece of 256 bytes starts at an
+    // arbitrary address, so the tiles left and right of a column boundary share a 128-byte line of every row, and as
+    // neighbours on one XCD they meet it in the same L2 (the second fetch and the two partial writes of a merge stop
+    // there) instead of each going to memory for it.  The grid holds 8 * ceil(tiles / 8) workgroups.
+    const int64_t total = ncx * nqy * G, chunk = (total + 7) >> 3;
+    const int64_t L = (int64_t)(blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (L >= total) return;                                 // (whole workgroups, before any barrier)
+    const int64_t cx = L % ncx, rest = L / ncx;
+    const int g = (int)(rest / nqy);
+    const int64_t q0 = (rest % nqy) * kTrQ, c0 = cx * kTrC;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     uint16_t *pack = sub + (int64_t)g * nr * nc;            // [nc][nr]
     uint32_t *W32 = reinterpret_cast<uint32_t *>(W);
@@ -501,10 +510,14 @@ static hipError_t copy_typed(const CopyArgs &a, hipStream_t st)
         tag_kernel(SCATTER ? "k_rows_transposed<scatter>" : "k_rows_transposed<gather>", 0.0, line_b);
         if (sizeof(E) == 2 && reinterpret_cast<uintptr_t>(W) % 4 == 0 && reinterpret_cast<uintptr_t>(sub) % 16 == 0 &&
             a.nr % 8 == 0 && ((int64_t)a.nr * a.nc) % 8 == 0 && a.G * a.nr == a.N_out) {
-            dim3 grid((unsigned)((a.nc + kTrC - 1) / kTrC), (unsigned)((a.nr + kTrQ - 1) / kTrQ), (unsigned)a.G);
-            hipLaunchKernelGGL((k_rows_transposed16<SCATTER>), grid, dim3(256), 0, st, reinterpret_cast<uint16_t *>(W), a.ld,
-                               reinterpret_cast<uint16_t *>(sub), a.rows, a.nr, a.nc);
-            return hipGetLastError();
+            const int64_t ncx = (a.nc + kTrC - 1) / kTrC, nqy = (a.nr + kTrQ - 1) / kTrQ;
+            const int64_t wgs = 8 * ((ncx * nqy * a.G + 7) / 8);
+            if (wgs < 0x7fffffffLL) {
+                hipLaunchKernelGGL((k_rows_transposed16<SCATTER>), dim3((unsigned)wgs), dim3(256), 0, st,
+                                   reinterpret_cast<uint16_t *>(W), a.ld, reinterpret_cast<uint16_t *>(sub), a.rows, a.nr, a.nc,
+                                   ncx, nqy, a.G);
+                return hipGetLastError();
+            }
         }
         dim3 grid((unsigned)((a.nc + 63) / 64), (unsigned)((a.nr + 63) / 64), (unsigned)a.G);
         hipLaunchKernelGGL((k_rows_transposed<E, SCATTER>), grid, dim3(256), 0, st, W, a.ld, sub,
