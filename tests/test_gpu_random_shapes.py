@@ -73,3 +73,69 @@ def test_random_shape_matches_oracle(case):
     np.testing.assert_allclose(loss_gpu, loss_orc, rtol=H.LOSS_RTOL[cfg.dtype], atol=1e-6)
     print(f"{cfg.name}: worst parameter rel err {worst:.3e} (tol {H.TOL[cfg.dtype]})")
     ctx.close()
+
+
+@pytest.mark.parametrize("case", range(24, 40))
+def test_random_shape_through_full_forward_and_resampling(case):
+    """The other entry points on shapes of the same draw: the full-network forward pass against the oracle
+    (and its variant with the library's own scratch memory against it, bit for bit), local steps after it
+    (it uses the same workspace), and two re-samplings against ist_merge followed by ist_partition."""
+    from paper_1910_02120_amd import ISTError
+    cfg, has_bias, normalize = draw(case)
+    print(f"{cfg.name}: {cfg.dtype} {cfg.input} dims={cfg.dims} S={cfg.S} B={cfg.B} k={cfg.k} "
+          f"standardised={normalize} bias={has_bias}", flush=True)
+    dev = "cuda:0"
+    P = H.Problem(cfg, has_bias=has_bias, dev=dev, normalize=normalize)
+    ctx = P.context()
+    got = ctx.forward_full(P.dW, P.db, cfg.B, X=P.dX, csr=P.dcsr)
+    torch.cuda.synchronize()
+    bs = P.bs if has_bias else None
+    if cfg.input == "csr":
+        rp, ci, va = orc.csr_slice(P.rp, P.ci, P.va, 0, cfg.B)
+        want = orc.forward_full(P.Ws, bs, cfg.dtype, csr=(rp, ci, va.astype(np.float64)), normalize=normalize)
+    else:
+        want = orc.forward_full(P.Ws, bs, cfg.dtype, X=P.X.reshape(-1, cfg.dims[0])[:cfg.B], normalize=normalize)
+    den = float(np.max(np.abs(want)))
+    err = float(np.max(np.abs(got.cpu().numpy().astype(np.float64) - want))) / (den if den > 0 else 1.0)
+    assert err <= H.TOL[cfg.dtype], (cfg.name, "full forward", err)
+    try:
+        again = torch.empty_like(got)
+        ctx.forward_full(P.dW, P.db, cfg.B, X=P.dX, csr=P.dcsr, logits=again, static=True)
+        torch.cuda.synchronize()
+        assert torch.equal(again, got), (cfg.name, "static scratch")
+    except ISTError as e:          # a network too large for the static array says so
+        assert "static scratch" in str(e), str(e)
+    ctx.partition(P.dW, P.db, P.dperm)
+    subs = H.copy_subnets(P.oracle_subnets())
+    loss_gpu = P.gpu_steps(ctx, k=cfg.k)
+    loss_orc = P.oracle_steps(subs, k=cfg.k)
+    H.compare_subnets(H.export_all(ctx, cfg), subs, cfg, H.TOL[cfg.dtype])
+    np.testing.assert_allclose(loss_gpu, loss_orc, rtol=H.LOSS_RTOL[cfg.dtype], atol=1e-6)
+    ctx.close()
+
+    a, b = P.context(), P.context()
+    Wa, Wb = [w.clone() for w in P.dW], [w.clone() for w in P.dW]
+    ba = [x.clone() for x in P.db] if has_bias else None
+    bb = [x.clone() for x in P.db] if has_bias else None
+    a.partition(Wa, ba, P.dperm)
+    b.partition(Wb, bb, P.dperm)
+    for rnd in (1, 2):
+        P.gpu_steps(a, loss=False)
+        P.gpu_steps(b, loss=False)
+        perm = [torch.from_numpy(p).to(dev) for p in gen.make_perms(cfg, rnd)]
+        a.resample(Wa, ba, perm)
+        b.merge(Wb, bb)
+        b.partition(Wb, bb, perm)
+        torch.cuda.synchronize()
+        for l in range(cfg.t):
+            assert torch.equal(Wa[l], Wb[l]), (cfg.name, rnd, l, "merged weights")
+            if has_bias:
+                assert torch.equal(ba[l], bb[l]), (cfg.name, rnd, l, "merged bias")
+        ga, gb = H.export_all(a, cfg), H.export_all(b, cfg)
+        for s in range(cfg.S):
+            for l in range(cfg.t):
+                assert torch.equal(ga[s][0][l], gb[s][0][l]), (cfg.name, rnd, s, l, "new subnet weights")
+                if has_bias:
+                    assert torch.equal(ga[s][1][l], gb[s][1][l]), (cfg.name, rnd, s, l, "new subnet bias")
+    a.close()
+    b.close()
