@@ -59,6 +59,9 @@ SHAPES = {
     # the logits with 256 x 256 blocks (264 = 256 + 8 hidden neurons per subnet, 10500 = 41 x 256 + 4 classes: the
     # transposed dz pass walks a grid of 42 x 1 blocks per subnet, five bands of 8 block rows and one of 2)
     "wide-out-gemm-bf16": _mk("wide-out-gemm-bf16", "cfg3", dims=(100, 2112, 10500), S=8, B=256, k=2, lr=0.5),
+    # hidden layers of at least 2048 neurons per subnet in f32: the bias kernel for wide layers (16-byte loads, eight
+    # columns per lane) in its f32 form, with a batch that is not a multiple of its row groups
+    "wide-hidden-f32": _mk("wide-hidden-f32", "cfg2", dims=(40, 4200, 4400, 7), S=2, B=70, k=2, lr=0.05),
     # more layers than one bias launch, one bias-copy launch or one shared update launch takes (16 / 16 / 4);
     # initial weights 1.5 x Xavier so that the gradient survives the 18 ReLU layers down to the first
     "very-deep-f32": _mk("very-deep-f32", "cfg2", dims=(16,) + (32,) * 18 + (5,), S=2, B=6, k=2, lr=0.05,
