@@ -43,6 +43,9 @@ MEASURED_TRAFFIC = {
     # the three update products of a step and their bias updates in one launch:
     # read 77.05 MB (FETCH_SIZE 37623.1 KiB x 2.000) + written 34.16 MB (WRITE_SIZE 33360.7 KiB x 1.000)
     "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3_bias": 111.21e6},
+    # the two 128 x 128 update products of a step (first and second layer, averaged): read 54.76 MB (26738.7 KiB x 2.000)
+    # + written 33.55 MB
+    "cfg3": {"gemm_update_bf16_128x128_t256_persistent": 88.31e6},
     "cfg4": {
         # read 1797.7 MB (877819.1 KiB x 2.000) + written 894.8 MB (873813.3 KiB x 1.000), average of the three layers
         "gemm_update_bf16_256x256_t512_persistent": 2692.5e6,
