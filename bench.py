@@ -40,6 +40,14 @@ EVENT_OVERHEAD_US = 2.4
 # device copies this script starts with; the runs and the scale factors are in profiles/.
 # {workload: {kernel label: bytes}}.  A dominant kernel without an entry is an error: re-measure.
 MEASURED_TRAFFIC = {
+    # the tiny network: every kernel takes about 5 us and any of them can come out on top
+    "cfg1": {
+        "gemm_bwd_data_f32_64x64_t256": 0.113e6,                       # read 0.097 MB (47.4 KiB x 2.000) + written 0.016 MB
+        "gemm_fwd_relu_f32_64x64_t256": 0.111e6,                       # read 0.095 MB + written 0.016 MB
+        "gemm_fwd_logits_f32_64x64_t256": 0.069e6,                     # read 0.065 MB + written 0.004 MB
+        "gemm_update_f32_64x64_t256_persistent_x3_bias": 0.411e6,      # read 0.339 MB + written 0.072 MB
+        "softmax_xent": 0.084e6,                                       # read 0.079 MB + written 0.005 MB
+    },
     # the three update products of a step and their bias updates in one launch:
     # read 77.05 MB (FETCH_SIZE 37623.1 KiB x 2.000) + written 34.16 MB (WRITE_SIZE 33360.7 KiB x 1.000)
     "cfg2": {"gemm_update_f32_64x64_t256_persistent_x3_bias": 111.21e6},
@@ -53,6 +61,11 @@ MEASURED_TRAFFIC = {
         "gemm_fwd_relu_bf16_256x256_t512": 1074.9e6,
         # read 1275.4 MB + written 67.1 MB
         "gemm_bwd_data_bf16_256x256_t512": 1342.5e6,
+    },
+    "speech8192": {
+        "gemm_fwd_relu_f32_64x64_t1024": 79.81e6,                      # read 75.62 MB + written 4.19 MB
+        "gemm_update_f32_128x128_t256_persistent": 319.34e6,           # read 185.10 MB + written 134.24 MB
+        "gemm_update_f32_64x64_t256_persistent_x3_bias": 229.90e6,     # read 161.54 MB + written 68.36 MB
     },
     "cfg5": {
         # backward launch of the wide output layer: read 1407.7 MB (687385.7 KiB x 2.000) + written 1421.3 MB
